@@ -1,0 +1,197 @@
+/*
+ * mdnn_oracle.c -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * A plain, slow, obviously-correct CPU statement of the forward-propagation
+ * (FPROP) minibatch convolution defined in Section 2 of the maxDNN paper
+ * (arXiv 1501.06633): Nb multi-channel maps against a bank of No multi-channel
+ * Sk x Sk filters, per-channel products summed over channels, a stride, an
+ * optional padding offset with the image sitting in an apron of zeros, and a
+ * final scale by a scalar alpha.
+ *
+ * It exists only so that tests, the smoke check and the benchmark's CPU
+ * baseline leg have something independent to compare the GPU library with.
+ * It shares no source, header, table or helper with the HIP path, and the HIP
+ * path never calls it.
+ *
+ * Data layout (Section 3, first paragraph: the innermost dimension is the
+ * batch for maps and the filter count for filters; the outer dimensions are
+ * width, height and channel):
+ *     in   [Nc][Hi][Wi][Nb]     fp32
+ *     filt [Nc][Sk][Sk][No]     fp32   (row k=(c*Sk+ky)*Sk+kx of a K x No matrix)
+ *     out  [No][Ho][Wo][Nb]     fp32
+ *
+ * Arithmetic: every product and every sum is taken in double; the result is
+ * scaled by alpha in double and rounded to fp32 exactly once.
+ *
+ * Readings taken where the paper gives no formula:
+ *   - cross-correlation (no filter flip): patch column k multiplies filter row
+ *     k (Section 3, the patch-times-filter-matrix statement);
+ *   - output size  Wo = floor((Wi + 2*pad - Sk)/stride) + 1  (it reproduces the
+ *     input/output/kernel triples of Table 1);
+ *   - one symmetric pad on all four sides, zeros outside the image;
+ *   - alpha is applied once to the finished sum; out is overwritten.
+ *
+ * Pins (tests/test_oracle_*.py, CPU only): brute-force im2col x GEMM in numpy
+ * float64, the 1x1/stride-1 = plain matrix product identity, delta filters,
+ * linearity in alpha / additivity, the all-ones closed form, exact-integer
+ * data, translation equivariance, torch.nn.functional.conv2d in float64, the
+ * Table 1 output sizes and hand-computed values of the complexity formula.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Output extent of one spatial dimension; returns 0 on success, 1 when the
+ * arguments admit no output (filter larger than the padded image, etc.). */
+int mdnn_oracle_out_dims(int Wi, int Hi, int Sk, int stride, int pad,
+                         int* Wo, int* Ho)
+{
+    if (Wi < 1 || Hi < 1 || Sk < 1 || stride < 1 || pad < 0) return 1;
+    if (Sk > Wi + 2 * pad || Sk > Hi + 2 * pad) return 1;
+    *Wo = (Wi + 2 * pad - Sk) / stride + 1;
+    *Ho = (Hi + 2 * pad - Sk) / stride + 1;
+    return 0;
+}
+
+/* Algorithmic complexity, Section 2:  2 Nb Wo Ho (Nc Sk^2 + 1) No  FLOPs. */
+uint64_t mdnn_oracle_flops(int Nb, int Wo, int Ho, int Nc, int No, int Sk)
+{
+    uint64_t per_output = (uint64_t)Nc * (uint64_t)Sk * (uint64_t)Sk + 1u;
+    return 2u * (uint64_t)Nb * (uint64_t)Wo * (uint64_t)Ho * per_output * (uint64_t)No;
+}
+
+int mdnn_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/*
+ * Whole-tensor convolution.  All pointers are HOST memory.
+ *   abs_sum  nullable; when given, receives for every output the sum of the
+ *            absolute values of the products that went into it (the scale
+ *            the acceptance tolerance is stated against), same layout as out.
+ *   nthreads <= 0 means "all the OpenMP runtime offers".
+ * Returns 0, or 1 on invalid dimensions / null pointers / allocation failure.
+ *
+ * The seven loops are o, y, x, c, ky, kx, n with n innermost (n is the
+ * contiguous index of both in and out); OpenMP splits the o loop and nothing
+ * else is blocked, fused or reordered.
+ */
+int mdnn_oracle_conv_fprop(const float* in, const float* filt, float* out,
+                           double* abs_sum,
+                           int Nb, int Wi, int Hi, int Nc, int No,
+                           int Sk, int stride, int pad, float alpha,
+                           int nthreads)
+{
+    int Wo, Ho;
+    if (!in || !filt || !out) return 1;
+    if (Nb < 1 || Nc < 1 || No < 1) return 1;
+    if (mdnn_oracle_out_dims(Wi, Hi, Sk, stride, pad, &Wo, &Ho)) return 1;
+#ifdef _OPENMP
+    if (nthreads <= 0) nthreads = omp_get_max_threads();
+#else
+    nthreads = 1;
+#endif
+    int failed = 0;
+
+#pragma omp parallel num_threads(nthreads)
+    {
+        double* S = (double*)malloc(sizeof(double) * (size_t)Nb);
+        double* A = (double*)malloc(sizeof(double) * (size_t)Nb);
+        if (!S || !A) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for schedule(dynamic, 1)
+            for (int o = 0; o < No; ++o) {
+                for (int y = 0; y < Ho; ++y) {
+                    for (int x = 0; x < Wo; ++x) {
+                        for (int n = 0; n < Nb; ++n) { S[n] = 0.0; A[n] = 0.0; }
+                        for (int c = 0; c < Nc; ++c) {
+                            for (int ky = 0; ky < Sk; ++ky) {
+                                int iy = y * stride - pad + ky;
+                                if (iy < 0 || iy >= Hi) continue;      /* zero apron */
+                                for (int kx = 0; kx < Sk; ++kx) {
+                                    int ix = x * stride - pad + kx;
+                                    if (ix < 0 || ix >= Wi) continue;  /* zero apron */
+                                    const float* row =
+                                        in + (((size_t)c * Hi + iy) * Wi + ix) * (size_t)Nb;
+                                    double w = (double)
+                                        filt[(((size_t)c * Sk + ky) * Sk + kx) * (size_t)No + o];
+                                    for (int n = 0; n < Nb; ++n) {
+                                        double p = (double)row[n] * w;
+                                        S[n] += p;
+                                        A[n] += fabs(p);
+                                    }
+                                }
+                            }
+                        }
+                        size_t base = (((size_t)o * Ho + y) * Wo + x) * (size_t)Nb;
+                        for (int n = 0; n < Nb; ++n)
+                            out[base + n] = (float)((double)alpha * S[n]);
+                        if (abs_sum)
+                            for (int n = 0; n < Nb; ++n) abs_sum[base + n] = A[n];
+                    }
+                }
+            }
+        }
+        free(S);
+        free(A);
+    }
+    return failed;
+}
+
+/*
+ * The same definition evaluated at a list of output positions only, one by
+ * one, so that a parity test at full layer size can check sampled outputs.
+ *   idx      npts x 4 ints: (o, y, x, n) per point
+ *   out_val  npts floats   (alpha * sum, rounded once)
+ *   abs_val  npts doubles  (sum of |products|), nullable
+ * Returns 0, or 1 on invalid arguments (including an index out of range).
+ */
+int mdnn_oracle_conv_fprop_points(const float* in, const float* filt,
+                                  const int32_t* idx, int64_t npts,
+                                  float* out_val, double* abs_val,
+                                  int Nb, int Wi, int Hi, int Nc, int No,
+                                  int Sk, int stride, int pad, float alpha)
+{
+    int Wo, Ho;
+    if (!in || !filt || !idx || !out_val || npts < 0) return 1;
+    if (Nb < 1 || Nc < 1 || No < 1) return 1;
+    if (mdnn_oracle_out_dims(Wi, Hi, Sk, stride, pad, &Wo, &Ho)) return 1;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t i = 0; i < npts; ++i) {
+        int o = idx[4 * i + 0], y = idx[4 * i + 1], x = idx[4 * i + 2], n = idx[4 * i + 3];
+        if (o < 0 || o >= No || y < 0 || y >= Ho || x < 0 || x >= Wo || n < 0 || n >= Nb) {
+            bad |= 1;
+            continue;
+        }
+        double S = 0.0, A = 0.0;
+        for (int c = 0; c < Nc; ++c)
+            for (int ky = 0; ky < Sk; ++ky)
+                for (int kx = 0; kx < Sk; ++kx) {
+                    int iy = y * stride - pad + ky;
+                    int ix = x * stride - pad + kx;
+                    if (iy < 0 || iy >= Hi || ix < 0 || ix >= Wi) continue;
+                    double p = (double)in[(((size_t)c * Hi + iy) * Wi + ix) * (size_t)Nb + n] *
+                               (double)filt[(((size_t)c * Sk + ky) * Sk + kx) * (size_t)No + o];
+                    S += p;
+                    A += fabs(p);
+                }
+        out_val[i] = (float)((double)alpha * S);
+        if (abs_val) abs_val[i] = A;
+    }
+    return bad;
+}

@@ -1,0 +1,91 @@
+"""Seeded synthetic layer workloads: shapes and input tensors only.
+
+This module holds none of the convolution's arithmetic (not even the output
+size): it names layer geometries and draws input / filter values.  Both the
+GPU parity tests and the CPU oracle's tests take their data from here so that
+the two sides see the same bytes.
+
+The five named layers follow the usual AlexNet / VGG layer geometries (image
+-like dense first layer, post-ReLU-like half-zero activations afterwards,
+small zero-mean Gaussian weights); they stand in for trained networks, which
+are not needed to time or check a convolution.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, asdict
+
+import numpy as np
+
+SEED_BASE = 150106633
+
+
+@dataclass(frozen=True)
+class Layer:
+    name: str
+    Nb: int
+    Hi: int
+    Wi: int
+    Nc: int
+    No: int
+    Sk: int
+    stride: int
+    pad: int
+    alpha: float
+    in_dist: str      # "uniform_pm1" | "uniform01" | "uniform01_relu"
+    filt_dist: str    # "uniform_pm1" | "normal_0p01"
+    seed: int
+
+    def dims(self) -> dict:
+        d = asdict(self)
+        return {k: d[k] for k in ("Nb", "Hi", "Wi", "Nc", "No", "Sk", "stride", "pad", "alpha")}
+
+
+LAYERS = {
+    "tiny":  Layer("tiny",    8,  32,  32,  16,  32,  3, 1, 1, 1.0, "uniform_pm1",    "uniform_pm1", SEED_BASE + 0),
+    "conv1": Layer("conv1", 128, 227, 227,   3,  96, 11, 4, 0, 1.0, "uniform01",      "normal_0p01", SEED_BASE + 1),
+    "conv2": Layer("conv2", 128,  27,  27,  96, 256,  5, 1, 2, 1.0, "uniform01_relu", "normal_0p01", SEED_BASE + 2),
+    "conv3": Layer("conv3", 128,  13,  13, 256, 384,  3, 1, 1, 1.0, "uniform01_relu", "normal_0p01", SEED_BASE + 3),
+    "vgg":   Layer("vgg",    64,  56,  56, 256, 256,  3, 1, 1, 0.5, "uniform01_relu", "normal_0p01", SEED_BASE + 4),
+}
+ORDER = ("tiny", "conv1", "conv2", "conv3", "vgg")
+
+
+def custom(name, Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha=1.0,
+           in_dist="uniform_pm1", filt_dist="uniform_pm1", seed=SEED_BASE + 1000) -> Layer:
+    return Layer(name, Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha, in_dist, filt_dist, seed)
+
+
+def make_inputs(layer: Layer):
+    """Return (inp, filt): float32, C-contiguous, shapes (Nc,Hi,Wi,Nb) and
+    (Nc,Sk,Sk,No).  Draw order: input values, zero mask (if any), filters."""
+    rng = np.random.Generator(np.random.PCG64(layer.seed))
+    ishape = (layer.Nc, layer.Hi, layer.Wi, layer.Nb)
+    fshape = (layer.Nc, layer.Sk, layer.Sk, layer.No)
+    if layer.in_dist == "uniform_pm1":
+        inp = rng.uniform(-1.0, 1.0, size=ishape).astype(np.float32)
+    elif layer.in_dist == "uniform01":
+        inp = rng.random(size=ishape, dtype=np.float32)
+    elif layer.in_dist == "uniform01_relu":
+        inp = rng.random(size=ishape, dtype=np.float32)
+        keep = rng.integers(0, 2, size=ishape, dtype=np.uint8)
+        inp *= keep
+    else:
+        raise ValueError(layer.in_dist)
+    if layer.filt_dist == "uniform_pm1":
+        filt = rng.uniform(-1.0, 1.0, size=fshape).astype(np.float32)
+    elif layer.filt_dist == "normal_0p01":
+        filt = (rng.standard_normal(size=fshape, dtype=np.float32) * np.float32(0.01))
+    else:
+        raise ValueError(layer.filt_dist)
+    return np.ascontiguousarray(inp), np.ascontiguousarray(filt)
+
+
+def make_int_inputs(layer: Layer, lo=-4, hi=4):
+    """Small-integer valued float32 tensors of the layer's shape: every partial
+    sum stays below 2**24, so any summation order gives the same fp32 result."""
+    rng = np.random.Generator(np.random.PCG64(layer.seed + 7919))
+    ishape = (layer.Nc, layer.Hi, layer.Wi, layer.Nb)
+    fshape = (layer.Nc, layer.Sk, layer.Sk, layer.No)
+    inp = rng.integers(lo, hi + 1, size=ishape).astype(np.float32)
+    filt = rng.integers(lo, hi + 1, size=fshape).astype(np.float32)
+    return inp, filt
