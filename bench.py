@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""FPROP convolution benchmark: TFLOP/s by the complexity formula of Section 2
+of the maxDNN paper, and the fraction of MI355X's FP32 matrix peak (the
+"computational efficiency" of Section 3.3, credited only for required FLOPs).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload vgg]
+                    [--variant NAME] [--no-layers] [--no-cpu-baseline] [--no-probe]
+
+A step is one whole FPROP convolution of the named layer (one launch of
+mdnn_conv_fprop) on seeded synthetic tensors already resident in HBM.  One
+JSON line goes to stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MATRIX_TFLOPS = 157.3      # 256 CUs x 256 FLOP/clk x 2.4 GHz
+PEAK_HBM_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_layer(torch, B, layer, d_in, d_f, out, steps, warmup, variant):
+    """Events on the launch stream (torch's current stream) around `steps` launches."""
+    for _ in range(warmup):
+        B.mdnn_conv_fprop(d_in, d_f, layer.stride, layer.pad, layer.alpha, out=out, variant=variant)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        B.mdnn_conv_fprop(d_in, d_f, layer.stride, layer.pad, layer.alpha, out=out, variant=variant)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return e0.elapsed_time(e1) / steps, wall_ms / steps
+
+
+def layer_report(torch, B, W, name, steps, warmup, variant=None):
+    L = W.LAYERS[name]
+    inp, filt = W.make_inputs(L)
+    d_in, d_f = torch.from_numpy(inp).cuda(), torch.from_numpy(filt).cuda()
+    st, Wo, Ho = B.mdnn_out_dims(L.Wi, L.Hi, L.Sk, L.stride, L.pad)
+    assert st == 0
+    out = torch.empty((L.No, Ho, Wo, L.Nb), dtype=torch.float32, device="cuda")
+    flops = B.mdnn_conv_flops(L.Nb, Wo, Ho, L.Nc, L.No, L.Sk)
+    ev_ms, wall_ms = time_layer(torch, B, L, d_in, d_f, out, steps, warmup, variant)
+    tflops = flops / (ev_ms * 1e-3) / 1e12
+    nbytes = 4 * (inp.size + filt.size + out.numel())
+    rep = {
+        "variant": variant or B.mdnn_choose_variant(L.Nb, L.Wi, L.Hi, L.Nc, L.No, L.Sk, L.stride, L.pad),
+        "ms": round(ev_ms, 5), "wall_ms": round(wall_ms, 5), "steps": steps,
+        "tflops": round(tflops, 3), "frac_peak": round(tflops / PEAK_FP32_MATRIX_TFLOPS, 4),
+        "flops": flops, "compulsory_bytes": nbytes,
+        "compulsory_GBps": round(nbytes / (ev_ms * 1e-3) / 1e9, 1),
+    }
+    return rep, (L, inp, filt, out)
+
+
+def cpu_baseline(W, name):
+    """The oracle as it stands, on a bounded sample: the first `No_s` filters of
+    the layer (all positions, whole batch), sized for roughly 10 s of CPU work."""
+    import numpy as np
+    import oracle
+
+    L = W.LAYERS[name]
+    inp, filt = W.make_inputs(L)
+    No_s = max(1, min(L.No, {"vgg": 96, "conv2": 192}.get(name, L.No)))
+    fs = np.ascontiguousarray(filt[..., :No_s])
+    Wo, Ho = oracle.out_dims(L.Wi, L.Hi, L.Sk, L.stride, L.pad)
+    flops = oracle.flops(L.Nb, Wo, Ho, L.Nc, No_s, L.Sk)
+    t0 = time.perf_counter()
+    oracle.conv_fprop(inp, fs, L.stride, L.pad, L.alpha, want_abs=False)
+    dt = time.perf_counter() - t0
+    return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.max_threads(),
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": f"first {No_s} of {L.No} output filters of layer {name}, all positions, whole batch"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="vgg", choices=["tiny", "conv1", "conv2", "conv3", "vgg"])
+    ap.add_argument("--variant", default=None, help="pin a tile variant for the headline workload")
+    ap.add_argument("--no-layers", action="store_true", help="skip the per-layer table")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probe", action="store_true", help="skip the register-only MFMA ceiling")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU by design (one convolution on one MI355X); "
+                 "run with --gpus 1")
+
+    import torch
+    from paper_1501_06633_amd import binding as B
+    from paper_1501_06633_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    B.lib()
+    torch.cuda.set_device(0)
+    props = torch.cuda.get_device_properties(0)
+    log(f"[bench] device={props.name} CUs={props.multi_processor_count}")
+
+    # ---- headline: K timed steps of the named workload
+    log(f"[bench] workload={args.workload} steps={args.steps} warmup={args.warmup}")
+    rep, _ = layer_report(torch, B, W, args.workload, args.steps, args.warmup, args.variant)
+    L = W.LAYERS[args.workload]
+    log(f"[bench] {args.workload}: {rep['ms']} ms/step, {rep['tflops']} TFLOP/s "
+        f"({100 * rep['frac_peak']:.1f}% of {PEAK_FP32_MATRIX_TFLOPS}) variant={rep['variant']}")
+
+    result = {
+        "metric": "conv FPROP TFLOP/s and % of MI355X FP32 matrix peak per layer shape",
+        "value": rep["tflops"], "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": rep["ms"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, **L.dims(), "variant": rep["variant"],
+                   "layout": "in CHWN, filt (C,Sk,Sk,No), out (No,Ho,Wo,Nb)"},
+        "roofline": {"bound": "mfma", "achieved": rep["tflops"], "peak": PEAK_FP32_MATRIX_TFLOPS,
+                     "unit": "TFLOP/s", "frac": rep["frac_peak"], "traffic": None},
+        "frac_of_fp32_matrix_peak": rep["frac_peak"],
+    }
+
+    # ---- register-only MFMA loop: what the matrix cores sustain with no memory traffic
+    if not args.no_probe:
+        sink = torch.zeros(2048 * 4 * 64, device="cuda")
+        for _ in range(2):
+            B.mdnn_mfma_peak_probe(sink, 2048, 4, 20000)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fl = 0
+        for _ in range(5):
+            fl += B.mdnn_mfma_peak_probe(sink, 2048, 4, 20000)
+        e1.record()
+        torch.cuda.synchronize()
+        ceiling = fl / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        result["mfma_f32_sustained_tflops"] = round(ceiling, 2)
+        result["frac_of_sustained"] = round(rep["tflops"] / ceiling, 4)
+        log(f"[bench] register-only FP32 MFMA loop: {ceiling:.1f} TFLOP/s sustained")
+
+    # ---- the other layer shapes (same launch path, fewer steps)
+    if not args.no_layers:
+        layers = {}
+        for name in W.ORDER:
+            if name == args.workload and args.variant is None:
+                layers[name] = rep
+                continue
+            steps = {"tiny": 200, "conv1": 50, "conv2": 50, "conv3": 100, "vgg": 30}[name]
+            r, _ = layer_report(torch, B, W, name, steps, 5)
+            layers[name] = r
+            log(f"[bench] {name}: {r['ms']} ms, {r['tflops']} TFLOP/s ({100 * r['frac_peak']:.1f}%) "
+                f"variant={r['variant']}")
+        result["layers"] = {k: {kk: v[kk] for kk in ("variant", "ms", "tflops", "frac_peak", "compulsory_GBps")}
+                            for k, v in layers.items()}
+
+    if not args.no_cpu_baseline:
+        log("[bench] timing the CPU oracle on a bounded sample ...")
+        result["cpu_baseline"] = cpu_baseline(W, args.workload)
+        log(f"[bench] oracle: {result['cpu_baseline']}")
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,110 @@
+/*
+ * mdnn.h -- C ABI of the MI355X (gfx950) forward-propagation convolution.
+ *
+ * The operation is the minibatch convolution of Section 2 of the maxDNN paper
+ * (arXiv 1501.06633), computed the way Sections 3 and 3.2 describe it: for
+ * every output coordinate, an Nb x (Sk^2 Nc) patch gathered from the
+ * batch-innermost input multiplies the (Sk^2 Nc) x No filter matrix, the
+ * gather offsets of the patch columns being precomputed once per tile.
+ *
+ * All functions are extern "C", throw nothing, keep no mutable global state
+ * that affects results, allocate no device memory and never synchronise the
+ * device.  Pointers named "device" are HIP device pointers; everything else
+ * is host memory.
+ */
+#ifndef MDNN_H_
+#define MDNN_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum mdnn_status {
+    MDNN_OK      = 0,
+    MDNN_EINVAL  = 1,   /* a dimension < 1, stride < 1, pad < 0, filter larger than padded image,
+                           non-finite alpha, unknown variant name */
+    MDNN_ENULL   = 2,   /* a required pointer is NULL */
+    MDNN_EALIGN  = 3,   /* a tensor pointer is not 16-byte aligned */
+    MDNN_ETOOBIG = 4,   /* a tensor is 2^32 bytes or larger (32-bit byte offsets are used on the
+                           device, the same kind of limit Section 3.1 notes for texture indices) */
+    MDNN_ELAUNCH = 5    /* the HIP runtime refused the launch (hipGetLastError() != hipSuccess) */
+} mdnn_status;
+
+/*
+ * FPROP convolution (Section 2; Section 3 for the layouts; Section 3.2 for the
+ * per-output-coordinate tiling and the offset table).
+ *
+ *   in    device, fp32, [Nc][Hi][Wi][Nb]   batch innermost, NOT physically padded
+ *   filt  device, fp32, [Nc][Sk][Sk][No]   = row-major (Nc*Sk*Sk) x No filter matrix
+ *   out   device, fp32, [No][Ho][Wo][Nb]   fully overwritten (no accumulate)
+ *
+ *   out[o][y][x][n] = alpha * sum_{c,ky,kx} in[c][y*stride-pad+ky][x*stride-pad+kx][n]
+ *                                         * filt[c][ky][kx][o]
+ *   with taps outside the image reading zero (the zero apron), and
+ *   Wo = floor((Wi + 2 pad - Sk)/stride) + 1, Ho likewise.
+ *
+ * Arithmetic is fp32 throughout (fp32 matrix-core FMAs, no reduced-precision
+ * conversion); the summation order is unspecified.  Any Nb >= 1 and No >= 1
+ * give correct results; the fast kernels need Nb % 4 == 0 and No % 4 == 0,
+ * other values take a slower scalar-load variant of the same kernel.
+ *
+ * The caller owns all three buffers; out must not overlap in or filt.  The
+ * call only enqueues work on `stream` (a hipStream_t; NULL = the default
+ * stream) and returns; the result is valid once the stream has been
+ * synchronised.  All argument checks happen before anything is enqueued:
+ * on any status other than MDNN_OK nothing has been launched.
+ */
+mdnn_status mdnn_conv_fprop(const float* in, const float* filt, float* out,
+                            int Nb, int Wi, int Hi, int Nc, int No,
+                            int Sk, int stride, int pad, float alpha,
+                            void* stream);
+
+/*
+ * Same operation with the tile variant chosen by the caller instead of the
+ * built-in heuristic (for tests and tuning).  `variant` is one of the names
+ * mdnn_variant_name() enumerates, or NULL / "" / "auto" for the heuristic.
+ * Every variant computes the same function for every valid argument set.
+ */
+mdnn_status mdnn_conv_fprop_variant(const float* in, const float* filt, float* out,
+                                    int Nb, int Wi, int Hi, int Nc, int No,
+                                    int Sk, int stride, int pad, float alpha,
+                                    void* stream, const char* variant);
+
+/* Output extents by the floor formula above (the paper gives none; this one
+ * reproduces every input/output/kernel triple of Table 1).  Host only. */
+mdnn_status mdnn_out_dims(int Wi, int Hi, int Sk, int stride, int pad, int* Wo, int* Ho);
+
+/* Algorithmic complexity of Section 2: 2 Nb Wo Ho (Nc Sk^2 + 1) No FLOPs.
+ * Returns 0 if any argument is < 1.  Host only. */
+uint64_t mdnn_conv_flops(int Nb, int Wo, int Ho, int Nc, int No, int Sk);
+
+/* Static, human-readable text for a status code.  Never NULL. */
+const char* mdnn_status_string(mdnn_status s);
+
+/* Name of tile variant number i (0 <= i < mdnn_variant_count()), else NULL. */
+int         mdnn_variant_count(void);
+const char* mdnn_variant_name(int i);
+
+/* Name of the variant the heuristic picks for a problem, without launching
+ * anything (host only).  Returns NULL if the geometry is invalid. */
+const char* mdnn_choose_variant(int Nb, int Wi, int Hi, int Nc, int No,
+                                int Sk, int stride, int pad);
+
+/*
+ * Measurement aid for the efficiency metric of Section 3.3 (actual over peak
+ * throughput): enqueue a register-only loop of fp32 matrix-core FMAs on every
+ * compute unit -- no memory traffic -- so that timing it gives the FP32 matrix
+ * rate the chip sustains under its power cap.  `sink` is a device buffer of at
+ * least 64 floats per launched wave (blocks * waves_per_block * 64 floats)
+ * that keeps the compiler from deleting the loop.  *flops receives the FLOPs
+ * one launch performs (host pointer, nullable).
+ */
+mdnn_status mdnn_mfma_peak_probe(float* sink, int blocks, int waves_per_block,
+                                 int iters, uint64_t* flops, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MDNN_H_ */

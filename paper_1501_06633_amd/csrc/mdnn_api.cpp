@@ -1,0 +1,206 @@
+// Host side of the C ABI: argument checks, geometry, the complexity formula,
+// tile-variant choice.  No HIP call happens in this file; launches go through
+// mdnn::launch_variant().
+#include <cmath>
+#include <cstring>
+
+#include "mdnn_internal.h"
+
+namespace {
+
+constexpr int     kComputeUnits = 256;          // MI355X
+constexpr int     kMaxTabEntries = 4096;        // 32 KB of LDS for the offset table
+constexpr int64_t kFourGiB = (int64_t)1 << 32;
+
+struct Geometry {
+    int     Wo, Ho;
+    int64_t K, M, in_bytes, filt_bytes, out_bytes;
+};
+
+mdnn_status check_geometry(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int pad,
+                           Geometry* g)
+{
+    if (Nb < 1 || Wi < 1 || Hi < 1 || Nc < 1 || No < 1 || Sk < 1 || stride < 1 || pad < 0)
+        return MDNN_EINVAL;
+    const int64_t Wp = (int64_t)Wi + 2 * (int64_t)pad, Hp = (int64_t)Hi + 2 * (int64_t)pad;
+    if (Sk > Wp || Sk > Hp) return MDNN_EINVAL;
+    if (Wp >= ((int64_t)1 << 30) || Hp >= ((int64_t)1 << 30)) return MDNN_ETOOBIG;
+    const int64_t Wo = (Wp - Sk) / stride + 1, Ho = (Hp - Sk) / stride + 1;
+    // sizes in 64-bit, factor by factor, so that nothing wraps before the limit check
+    auto bytes = [](int64_t a, int64_t b, int64_t c, int64_t d) -> int64_t {
+        int64_t v = 4;
+        const int64_t f[4] = {a, b, c, d};
+        for (int64_t x : f) {
+            if (v > kFourGiB / x) return kFourGiB;         // v*x would exceed 2^32
+            v *= x;
+        }
+        return v;
+    };
+    g->in_bytes   = bytes(Nc, Hi, Wi, Nb);
+    g->filt_bytes = bytes(Nc, Sk, Sk, No);
+    g->out_bytes  = bytes(No, Ho, Wo, Nb);
+    if (g->in_bytes >= kFourGiB || g->filt_bytes >= kFourGiB || g->out_bytes >= kFourGiB)
+        return MDNN_ETOOBIG;
+    g->Wo = (int)Wo;
+    g->Ho = (int)Ho;
+    g->K  = (int64_t)Nc * Sk * Sk;
+    g->M  = Ho * Wo * (int64_t)Nb;
+    return MDNN_OK;
+}
+
+int div_up(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+bool variant_usable(const mdnn::VariantInfo& v, int Nb, int No)
+{
+    return !v.vec || (Nb % 4 == 0 && No % 4 == 0);
+}
+
+// Cost of a variant: tiles are dealt to 256 compute units, a unit works through
+// its tiles one tile-time after another (co-resident workgroups share the
+// matrix pipe, they do not add to it), and a tile costs its full area even
+// when it hangs over the edge of the output matrix (Section 3.3's point about
+// credit for unnecessary work).
+double variant_cost(const mdnn::VariantInfo& v, int No, int64_t M)
+{
+    const int64_t tiles  = (int64_t)div_up(No, v.tile_o) * div_up(M, v.tile_m);
+    const int64_t rounds = (tiles + kComputeUnits - 1) / kComputeUnits;
+    return (double)rounds * v.tile_o * v.tile_m / v.eff;
+}
+
+int choose(int Nb, int No, int64_t M)
+{
+    int    best = -1;
+    double best_cost = 0;
+    for (int i = 0; i < mdnn::variant_count(); ++i) {
+        const mdnn::VariantInfo& v = mdnn::variant_info(i);
+        if (!variant_usable(v, Nb, No)) continue;
+        const double c = variant_cost(v, No, M);
+        if (best < 0 || c < best_cost) { best = i; best_cost = c; }
+    }
+    return best;
+}
+
+int find_variant(const char* name)
+{
+    for (int i = 0; i < mdnn::variant_count(); ++i)
+        if (std::strcmp(name, mdnn::variant_info(i).name) == 0) return i;
+    return -1;
+}
+
+}  // namespace
+
+extern "C" {
+
+mdnn_status mdnn_out_dims(int Wi, int Hi, int Sk, int stride, int pad, int* Wo, int* Ho)
+{
+    if (!Wo || !Ho) return MDNN_ENULL;
+    Geometry g;
+    // Nb = Nc = No = 1: only the spatial geometry matters here
+    const mdnn_status s = check_geometry(1, Wi, Hi, 1, 1, Sk, stride, pad, &g);
+    if (s != MDNN_OK) return s;
+    *Wo = g.Wo;
+    *Ho = g.Ho;
+    return MDNN_OK;
+}
+
+uint64_t mdnn_conv_flops(int Nb, int Wo, int Ho, int Nc, int No, int Sk)
+{
+    if (Nb < 1 || Wo < 1 || Ho < 1 || Nc < 1 || No < 1 || Sk < 1) return 0;
+    const uint64_t macs_per_output = (uint64_t)Nc * (uint64_t)Sk * (uint64_t)Sk + 1u;
+    const uint64_t outputs = (uint64_t)Nb * (uint64_t)Wo * (uint64_t)Ho * (uint64_t)No;
+    return 2u * outputs * macs_per_output;
+}
+
+const char* mdnn_status_string(mdnn_status s)
+{
+    switch (s) {
+        case MDNN_OK:      return "ok";
+        case MDNN_EINVAL:  return "invalid argument (dimension, stride, pad, alpha or variant name)";
+        case MDNN_ENULL:   return "null pointer";
+        case MDNN_EALIGN:  return "tensor pointer not 16-byte aligned";
+        case MDNN_ETOOBIG: return "tensor of 4 GiB or more";
+        case MDNN_ELAUNCH: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+int mdnn_variant_count(void) { return mdnn::variant_count(); }
+
+const char* mdnn_variant_name(int i)
+{
+    if (i < 0 || i >= mdnn::variant_count()) return nullptr;
+    return mdnn::variant_info(i).name;
+}
+
+const char* mdnn_choose_variant(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int pad)
+{
+    Geometry g;
+    if (check_geometry(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &g) != MDNN_OK) return nullptr;
+    const int v = choose(Nb, No, g.M);
+    return v < 0 ? nullptr : mdnn::variant_info(v).name;
+}
+
+mdnn_status mdnn_conv_fprop_variant(const float* in, const float* filt, float* out,
+                                    int Nb, int Wi, int Hi, int Nc, int No,
+                                    int Sk, int stride, int pad, float alpha,
+                                    void* stream, const char* variant)
+{
+    if (!in || !filt || !out) return MDNN_ENULL;
+    Geometry g;
+    const mdnn_status gs = check_geometry(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &g);
+    if (gs != MDNN_OK) return gs;
+    if (!std::isfinite(alpha)) return MDNN_EINVAL;
+    if (((uintptr_t)in | (uintptr_t)filt | (uintptr_t)out) & 15u) return MDNN_EALIGN;
+
+    int v;
+    if (!variant || !variant[0] || std::strcmp(variant, "auto") == 0) {
+        v = choose(Nb, No, g.M);
+    } else {
+        v = find_variant(variant);
+        if (v >= 0 && !variant_usable(mdnn::variant_info(v), Nb, No)) v = -1;
+    }
+    if (v < 0) return MDNN_EINVAL;
+    const mdnn::VariantInfo& vi = mdnn::variant_info(v);
+
+    mdnn::ConvParams p;
+    p.in = in;  p.filt = filt;  p.out = out;
+    p.Nb = Nb;  p.Wi = Wi;  p.Hi = Hi;  p.Nc = Nc;  p.No = No;
+    p.Sk = Sk;  p.stride = stride;  p.pad = pad;
+    p.Wo = g.Wo;  p.Ho = g.Ho;
+    p.K = (int)g.K;  p.SkSk = Sk * Sk;  p.M = (int)g.M;
+    p.n_otiles = div_up(No, vi.tile_o);
+    p.n_mtiles = div_up(g.M, vi.tile_m);
+    const int64_t n_tiles = (int64_t)p.n_otiles * p.n_mtiles;
+    if (n_tiles > ((int64_t)1 << 28)) return MDNN_ETOOBIG;
+    p.n_tiles = (int)n_tiles;
+    p.tiles_per_xcd = div_up(n_tiles, 8);
+    const int kpad = div_up(g.K, vi.kslab) * vi.kslab;
+    p.tab_cap = kpad < kMaxTabEntries ? kpad : kMaxTabEntries;
+    p.in_bytes = (uint32_t)g.in_bytes;
+    p.filt_bytes = (uint32_t)g.filt_bytes;
+    p.alpha = alpha;
+
+    return mdnn::launch_variant(v, p, stream) == 0 ? MDNN_OK : MDNN_ELAUNCH;
+}
+
+mdnn_status mdnn_conv_fprop(const float* in, const float* filt, float* out,
+                            int Nb, int Wi, int Hi, int Nc, int No,
+                            int Sk, int stride, int pad, float alpha, void* stream)
+{
+    return mdnn_conv_fprop_variant(in, filt, out, Nb, Wi, Hi, Nc, No, Sk, stride, pad, alpha,
+                                   stream, nullptr);
+}
+
+mdnn_status mdnn_mfma_peak_probe(float* sink, int blocks, int waves_per_block, int iters,
+                                 uint64_t* flops, void* stream)
+{
+    if (!sink) return MDNN_ENULL;
+    if (blocks < 1 || blocks > (1 << 20) || waves_per_block < 1 || waves_per_block > 4 || iters < 1)
+        return MDNN_EINVAL;
+    // 4 MFMA 32x32x2 per iteration per wave, 2*32*32*2 FLOPs each
+    if (flops) *flops = (uint64_t)blocks * waves_per_block * (uint64_t)iters * 4u * 4096u;
+    return mdnn::launch_mfma_probe(sink, blocks, waves_per_block, iters, stream) == 0 ? MDNN_OK
+                                                                                      : MDNN_ELAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,56 @@
+// Internal interface between the host API (mdnn_api.cpp) and the kernel
+// translation unit (conv_fprop.hip).  Not installed; not part of the C ABI.
+#ifndef MDNN_INTERNAL_H_
+#define MDNN_INTERNAL_H_
+
+#include <stdint.h>
+#include "mdnn.h"
+
+namespace mdnn {
+
+// Everything a tile needs, passed by value as the single kernel argument.
+struct ConvParams {
+    const float* in;
+    const float* filt;
+    float*       out;
+    int Nb, Wi, Hi, Nc, No, Sk, stride, pad;
+    int Wo, Ho;
+    int K;               // Nc*Sk*Sk: rows of the filter matrix / columns of a patch (Section 3)
+    int SkSk;            // Sk*Sk
+    int M;               // Ho*Wo*Nb: columns of the output seen as a row-major No x M matrix
+    int n_otiles;        // tiles along No
+    int n_mtiles;        // tiles along M
+    int n_tiles;         // n_otiles * n_mtiles
+    int tiles_per_xcd;   // ceil(n_tiles / 8)
+    int tab_cap;         // offset-table entries resident in LDS at once (multiple of the K slab)
+    uint32_t in_bytes;   // byte size of in   (buffer-resource range: loads beyond it return 0)
+    uint32_t filt_bytes; // byte size of filt
+    float alpha;
+};
+
+// Static description of one tile variant (one template instantiation).
+struct VariantInfo {
+    const char* name;
+    int tile_o;          // output filters per workgroup tile
+    int tile_m;          // flat (coordinate, batch) columns per workgroup tile
+    int kslab;           // patch columns (k) staged in LDS per pipeline step
+    int threads;         // workgroup size
+    int vec;             // 1: 16-byte loads/stores, needs Nb % 4 == 0 and No % 4 == 0
+    int est_wg_per_cu;   // workgroups expected to be co-resident on one compute unit
+    float eff;           // sustained fraction of the matrix rate inside a full tile (measured)
+};
+
+int                variant_count();
+const VariantInfo& variant_info(int i);
+
+// LDS bytes variant i needs for a table of tab_cap entries.
+uint32_t variant_lds_bytes(int i, int tab_cap);
+
+// Enqueue variant i.  p.n_* / tab_cap must have been filled for that variant.
+// Returns hipSuccess (0) or the HIP error code as int.
+int launch_variant(int i, const ConvParams& p, void* stream);
+
+int launch_mfma_probe(float* sink, int blocks, int waves_per_block, int iters, void* stream);
+
+}  // namespace mdnn
+#endif

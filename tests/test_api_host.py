@@ -1,0 +1,137 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports
+every function include/mdnn.h declares, and rejects bad arguments before
+anything could be launched.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1501_06633_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mdnn.h")
+
+FAKE = 0x10000          # 16-byte aligned, never dereferenced: every call below fails validation first
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_1501_06633_amd import build
+        build.build_lib()
+    return B.lib()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mdnn_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_exports_every_declared_symbol(L):
+    names = declared_functions()
+    assert {"mdnn_conv_fprop", "mdnn_conv_fprop_variant", "mdnn_out_dims", "mdnn_conv_flops",
+            "mdnn_status_string", "mdnn_variant_count", "mdnn_variant_name",
+            "mdnn_choose_variant", "mdnn_mfma_peak_probe"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), f"libmdnn.so does not export {n}"
+
+
+def test_out_dims_and_flops_match_the_paper(L):
+    golden = os.path.join(ROOT, "tests", "golden")
+    for line in open(os.path.join(golden, "table1_shapes.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        _, _, Wi, _, Wo, _, Sk, stride, pad = line.split()
+        st, wo, ho = B.mdnn_out_dims(int(Wi), int(Wi), int(Sk), int(stride), int(pad))
+        assert (st, wo, ho) == (B.MDNN_OK, int(Wo), int(Wo)), line
+    for line in open(os.path.join(golden, "flops_values.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        Nb, Wo, Ho, Nc, No, Sk, C = map(int, line.split())
+        assert B.mdnn_conv_flops(Nb, Wo, Ho, Nc, No, Sk) == C, line
+    assert B.mdnn_out_dims(7, 5, 3, 1, 0) == (B.MDNN_OK, 5, 3)
+    assert B.mdnn_out_dims(8, 8, 3, 2, 0) == (B.MDNN_OK, 3, 3)
+    assert B.mdnn_conv_flops(0, 1, 1, 1, 1, 1) == 0
+
+
+def test_out_dims_errors(L):
+    assert B.mdnn_out_dims(5, 5, 6, 1, 0)[0] == B.MDNN_EINVAL
+    assert B.mdnn_out_dims(5, 5, 3, 0, 0)[0] == B.MDNN_EINVAL
+    assert B.mdnn_out_dims(5, 5, 3, 1, -1)[0] == B.MDNN_EINVAL
+    assert B.mdnn_out_dims(0, 5, 1, 1, 0)[0] == B.MDNN_EINVAL
+    assert L.mdnn_out_dims(5, 5, 3, 1, 0, None, None) == B.MDNN_ENULL
+
+
+GOOD = dict(Nb=8, Wi=32, Hi=32, Nc=16, No=32, Sk=3, stride=1, pad=1)
+
+
+def call(in_ptr=FAKE, filt_ptr=FAKE, out_ptr=FAKE, alpha=1.0, variant=None, **kw):
+    d = dict(GOOD)
+    d.update(kw)
+    return B.mdnn_conv_fprop_raw(in_ptr, filt_ptr, out_ptr, d["Nb"], d["Wi"], d["Hi"], d["Nc"], d["No"],
+                                 d["Sk"], d["stride"], d["pad"], alpha, None, variant)
+
+
+def test_null_pointers(L):
+    assert call(in_ptr=None) == B.MDNN_ENULL
+    assert call(filt_ptr=None) == B.MDNN_ENULL
+    assert call(out_ptr=None) == B.MDNN_ENULL
+
+
+@pytest.mark.parametrize("kw", [dict(Nb=0), dict(Wi=0), dict(Hi=-1), dict(Nc=0), dict(No=0), dict(Sk=0),
+                                dict(stride=0), dict(pad=-1), dict(Sk=35), dict(Sk=35, Wi=40), dict(Sk=35, Hi=40),
+                                dict(alpha=float("nan")), dict(alpha=float("inf"))])
+def test_invalid_arguments(L, kw):
+    assert call(**kw) == B.MDNN_EINVAL
+
+
+def test_too_big(L):
+    assert call(Nb=1024, Wi=1024, Hi=1024, Nc=1) == B.MDNN_ETOOBIG          # in = 4 GiB exactly
+    assert call(Nb=128, Wi=2048, Hi=2048, Nc=1, No=4) == B.MDNN_ETOOBIG     # out = 8 GiB
+    assert call(Nc=65536, Sk=3, No=4096) == B.MDNN_ETOOBIG                  # filt
+    assert call(Nb=2**20, Wi=2**20, Hi=2**20, Nc=2**20) == B.MDNN_ETOOBIG   # no wrap-around
+
+
+def test_misaligned(L):
+    assert call(in_ptr=FAKE + 4) == B.MDNN_EALIGN
+    assert call(filt_ptr=FAKE + 8) == B.MDNN_EALIGN
+    assert call(out_ptr=FAKE + 1) == B.MDNN_EALIGN
+
+
+def test_unknown_or_unusable_variant(L):
+    assert call(variant="no_such_tile") == B.MDNN_EINVAL
+    vec = [n for n in B.mdnn_variant_names() if not n.endswith("s")]
+    assert call(variant=vec[0], Nb=6) == B.MDNN_EINVAL       # 16-byte variant needs Nb % 4 == 0
+
+
+def test_variant_registry_and_choice(L):
+    names = B.mdnn_variant_names()
+    assert len(names) == len(set(names)) >= 3
+    assert L.mdnn_variant_name(-1) is None and L.mdnn_variant_name(len(names)) is None
+    for shape in [(8, 32, 32, 16, 32, 3, 1, 1), (128, 227, 227, 3, 96, 11, 4, 0),
+                  (128, 27, 27, 96, 256, 5, 1, 2), (64, 56, 56, 256, 256, 3, 1, 1),
+                  (7, 9, 9, 3, 5, 3, 1, 1)]:
+        assert B.mdnn_choose_variant(*shape) in names
+    assert B.mdnn_choose_variant(7, 9, 9, 3, 5, 3, 1, 1).endswith("s")     # scalar-load variant
+    assert B.mdnn_choose_variant(8, 2, 2, 1, 1, 3, 1, 0) is None          # invalid geometry
+
+
+def test_status_strings(L):
+    seen = {B.status_string(s) for s in range(6)}
+    assert len(seen) == 6 and all(seen)
+    assert B.status_string(99)
+
+
+def test_probe_argument_checks(L):
+    assert L.mdnn_mfma_peak_probe(None, 1, 1, 1, None, None) == B.MDNN_ENULL
+    assert L.mdnn_mfma_peak_probe(FAKE, 0, 1, 1, None, None) == B.MDNN_EINVAL
+    assert L.mdnn_mfma_peak_probe(FAKE, 1, 5, 1, None, None) == B.MDNN_EINVAL
+    assert L.mdnn_mfma_peak_probe(FAKE, 1, 1, 0, None, None) == B.MDNN_EINVAL
+
+
+def test_tensor_wrapper_refuses_cpu_tensors(L):
+    torch = pytest.importorskip("torch")
+    with pytest.raises(ValueError):
+        B.mdnn_conv_fprop(torch.zeros(2, 4, 4, 4), torch.zeros(2, 3, 3, 4), 1, 1)

@@ -1,0 +1,223 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.
+
+Acceptance bound (per output):  |gpu - oracle| <= 1e-4 * |alpha| * A  where A
+is the sum of |in * filt| over the taps of that output (the oracle returns it);
+where A == 0 the GPU value must be exactly zero.  A much tighter regression
+bound (TIGHT) is asserted as well: fp32 accumulation over K <= 2400 terms sits
+near 1e-6 * A, and a silent drop to a reduced-precision matrix format (~1e-3
+per product) would pass the loose bound at these K but not the tight one.
+Integer-valued inputs must match bit for bit (every partial sum is exact in
+fp32, so no summation order can change the result).
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_1501_06633_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+LOOSE = 1e-4
+TIGHT = 2e-5
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_1501_06633_amd import binding as B
+    B.lib()                                    # fail loudly if the HIP library is missing
+    import oracle
+    oracle.build(force=False)
+    return torch, B, oracle
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def run_gpu(env, layer, inp, filt, variant=None):
+    torch, B, _ = env
+    d_in = torch.from_numpy(inp).cuda()
+    d_f = torch.from_numpy(filt).cuda()
+    out = B.mdnn_conv_fprop(d_in, d_f, layer.stride, layer.pad, layer.alpha, variant=variant)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def check(got, want, absum, alpha, what):
+    err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    scale = abs(alpha) * absum
+    zero = scale == 0
+    assert (got[zero] == 0).all(), f"{what}: non-zero output where every product is zero"
+    ratio = np.zeros_like(err)
+    np.divide(err, scale, out=ratio, where=~zero)
+    worst = float(ratio.max()) if ratio.size else 0.0
+    say(f"    {what}: max |err|/(|alpha| A) = {worst:.3e} over {got.size} outputs")
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    assert worst <= LOOSE, f"{what}: acceptance bound exceeded ({worst:.3e})"
+    assert worst <= TIGHT, f"{what}: fp32-accumulation regression bound exceeded ({worst:.3e})"
+    return worst
+
+
+# ---------------------------------------------------------------- full layers
+@pytest.mark.parametrize("name", W.ORDER)
+def test_layer_matches_oracle_everywhere(env, name):
+    """All five layer shapes at full size, every output element, default variant
+    (the launch configuration bench.py times)."""
+    _, B, oracle = env
+    L = W.LAYERS[name]
+    say(f"[parity] layer={name} seed={L.seed} dims={L.dims()} "
+        f"variant={B.mdnn_choose_variant(L.Nb, L.Wi, L.Hi, L.Nc, L.No, L.Sk, L.stride, L.pad)}")
+    inp, filt = W.make_inputs(L)
+    got = run_gpu(env, L, inp, filt)
+    want, absum = oracle.conv_fprop(inp, filt, L.stride, L.pad, L.alpha)
+    assert got.shape == want.shape
+    check(got, want, absum, L.alpha, name)
+
+
+@pytest.mark.parametrize("name", W.ORDER)
+def test_layer_integer_data_bitwise(env, name):
+    """Full-size layers with small-integer data: sampled outputs (plus all four
+    corners of the output tensor) must equal the oracle bit for bit."""
+    _, B, oracle = env
+    L = W.LAYERS[name]
+    say(f"[parity-int] layer={name} seed={L.seed + 7919}")
+    inp, filt = W.make_int_inputs(L)
+    got = run_gpu(env, L, inp, filt)
+    No, Ho, Wo, Nb = got.shape
+    rng = np.random.default_rng(L.seed)
+    npts = 40000
+    idx = np.stack([rng.integers(0, No, npts), rng.integers(0, Ho, npts),
+                    rng.integers(0, Wo, npts), rng.integers(0, Nb, npts)], axis=1).astype(np.int32)
+    idx[0] = (0, 0, 0, 0)
+    idx[1] = (No - 1, Ho - 1, Wo - 1, Nb - 1)
+    idx[2] = (No - 1, 0, Wo - 1, 0)
+    idx[3] = (0, Ho - 1, 0, Nb - 1)
+    vals, _ = oracle.conv_fprop_points(inp, filt, idx, L.stride, L.pad, L.alpha)
+    o, y, x, n = idx.T
+    np.testing.assert_array_equal(got[o, y, x, n], vals)
+    assert np.abs(vals).max() > 0
+
+
+# ------------------------------------------------------- odd shapes, all variants
+ODD = [
+    # name              Nb  Hi  Wi  Nc  No  Sk st pad alpha
+    ("ragged_vec",      12, 11,  9,  5, 36, 3, 1, 1, 0.5),     # tails in No, M and K
+    ("ragged_scalar",    7, 10, 11,  3, 37, 3, 2, 1, 1.5),     # Nb, No not multiples of 4
+    ("nb1_no1",          1,  9,  9,  2,  1, 3, 1, 0, 1.0),
+    ("one_by_one",      16,  6,  7, 40, 24, 1, 1, 0, -2.0),    # plain matrix product
+    ("big_filter",       8, 12, 12,  3, 16, 7, 2, 3, 1.0),
+    ("filter_eq_image",  4,  5,  5,  4,  8, 5, 1, 0, 1.0),     # a single output coordinate
+    ("wide_apron",       8,  6,  6,  3, 12, 3, 1, 2, 1.0),     # pad close to Sk: whole rows of taps in the apron
+    ("stride3_nonsq",   20,  9, 14,  6, 40, 4, 3, 1, 0.25),
+    ("k_odd",            8,  8,  8,  3, 32, 3, 1, 1, 1.0),     # K = 27: odd, one partial slab
+    ("many_tiles",      32, 15, 13, 20, 200, 3, 1, 1, 1.0),    # several tiles both ways + tails
+    ("long_k_chunked",   8,  6,  6, 520, 32, 3, 1, 1, 1.0),    # K = 4680 > one offset-table chunk
+]
+
+
+@pytest.mark.parametrize("case", ODD, ids=[c[0] for c in ODD])
+def test_odd_shapes_every_usable_variant(env, case):
+    _, B, oracle = env
+    name, Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha = case
+    L = W.custom(name, Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha, seed=W.SEED_BASE + 100 + len(name))
+    inp, filt = W.make_inputs(L)
+    want, absum = oracle.conv_fprop(inp, filt, stride, pad, alpha)
+    ran = 0
+    for variant in [None] + B.mdnn_variant_names():
+        if variant is not None and not variant.endswith("s") and (Nb % 4 or No % 4):
+            continue
+        say(f"[parity-odd] case={name} variant={variant} dims={L.dims()}")
+        got = run_gpu(env, L, inp, filt, variant)
+        check(got, want, absum, alpha, f"{name}/{variant}")
+        ran += 1
+    assert ran >= 2
+
+
+def test_mid_size_all_variants_integer_bitwise(env):
+    """One mid-size shape that spans many tiles of every variant, integer data,
+    whole tensor compared bit for bit -- also a race detector for the LDS
+    double buffering."""
+    _, B, oracle = env
+    L = W.custom("mid", 64, 14, 14, 48, 288, 3, 1, 1, 0.5)
+    inp, filt = W.make_int_inputs(L)
+    want = oracle.conv_fprop(inp, filt, L.stride, L.pad, L.alpha, want_abs=False)
+    for variant in B.mdnn_variant_names():
+        say(f"[parity-mid] variant={variant}")
+        got = run_gpu(env, L, inp, filt, variant)
+        np.testing.assert_array_equal(got, want, err_msg=variant)
+
+
+# ------------------------------------------------------------ semantic edge cases
+def test_delta_filter_and_apron_zeros(env):
+    _, B, _ = env
+    L = W.custom("delta", 8, 9, 8, 4, 8, 3, 1, 1, 2.0)
+    inp, _ = W.make_inputs(L)
+    filt = np.zeros((L.Nc, L.Sk, L.Sk, L.No), np.float32)
+    c0, ky0, kx0, o0 = 2, 0, 2, 5
+    filt[c0, ky0, kx0, o0] = 1.0
+    say("[parity-delta]")
+    got = run_gpu(env, L, inp, filt)
+    want = np.zeros_like(got)
+    for y in range(got.shape[1]):
+        for x in range(got.shape[2]):
+            iy, ix = y - L.pad + ky0, x - L.pad + kx0
+            if 0 <= iy < L.Hi and 0 <= ix < L.Wi:
+                want[o0, y, x, :] = 2.0 * inp[c0, iy, ix, :]
+    np.testing.assert_array_equal(got, want)
+
+
+def test_alpha_zero_and_determinism(env):
+    torch, B, _ = env
+    L = W.LAYERS["tiny"]
+    inp, filt = W.make_inputs(L)
+    d_in, d_f = torch.from_numpy(inp).cuda(), torch.from_numpy(filt).cuda()
+    say("[parity-alpha0]")
+    z = B.mdnn_conv_fprop(d_in, d_f, L.stride, L.pad, 0.0)
+    a = B.mdnn_conv_fprop(d_in, d_f, L.stride, L.pad, 1.0)
+    b = B.mdnn_conv_fprop(d_in, d_f, L.stride, L.pad, 1.0)
+    torch.cuda.synchronize()
+    assert not z.cpu().numpy().any()
+    assert torch.equal(a, b)
+
+
+def test_output_is_overwritten_not_accumulated(env):
+    torch, B, oracle = env
+    L = W.custom("ow", 8, 8, 8, 4, 16, 3, 1, 1, 1.0)
+    inp, filt = W.make_int_inputs(L)
+    d_in, d_f = torch.from_numpy(inp).cuda(), torch.from_numpy(filt).cuda()
+    out = torch.full((16, 8, 8, 8), float("nan"), device="cuda")
+    say("[parity-overwrite]")
+    B.mdnn_conv_fprop(d_in, d_f, 1, 1, 1.0, out=out)
+    torch.cuda.synchronize()
+    want = oracle.conv_fprop(inp, filt, 1, 1, 1.0, want_abs=False)
+    np.testing.assert_array_equal(out.cpu().numpy(), want)
+
+
+def test_runs_on_a_side_stream(env):
+    torch, B, oracle = env
+    L = W.custom("stream", 16, 10, 10, 8, 32, 3, 1, 1, 1.0)
+    inp, filt = W.make_int_inputs(L)
+    d_in, d_f = torch.from_numpy(inp).cuda(), torch.from_numpy(filt).cuda()
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    say("[parity-stream]")
+    with torch.cuda.stream(s):
+        out = B.mdnn_conv_fprop(d_in, d_f, 1, 1, 1.0)
+    s.synchronize()
+    want = oracle.conv_fprop(inp, filt, 1, 1, 1.0, want_abs=False)
+    np.testing.assert_array_equal(out.cpu().numpy(), want)
+
+
+def test_mfma_probe_runs(env):
+    torch, B, _ = env
+    sink = torch.zeros(256 * 4 * 64, device="cuda")
+    say("[probe]")
+    flops = B.mdnn_mfma_peak_probe(sink, 256, 4, 100)
+    torch.cuda.synchronize()
+    assert flops == 256 * 4 * 100 * 4 * 4096
+    assert torch.isfinite(sink).all() and float(sink.abs().sum()) > 0
