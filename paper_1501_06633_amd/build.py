@@ -41,6 +41,7 @@ def build_lib(force: bool = True, extra_flags=()) -> str:
         noise = "is not a recognized feature for this target"
         out = "\n".join(l for l in res.stdout.splitlines() if noise not in l)
         if res.returncode != 0:
+            print(out)
             raise subprocess.CalledProcessError(res.returncode, cmd, output=out)
         if out.strip():
             print(out)

@@ -24,7 +24,18 @@
 // patch base + table[k].  The image is not physically padded: a tap in the
 // zero apron gets an out-of-range buffer offset, for which the hardware
 // returns 0, so the inner loop has no boundary branch.
+//
+// Pipeline (the paper's Section 3.1 double buffering, re-cut for CDNA4):
+// operand slabs of KS patch columns go global -> LDS directly
+// (buffer_load ... lds, no staging registers) into a ring of NS stages, NS-1
+// slabs ahead of the MFMAs; one workgroup barrier per slab; inside a slab the
+// LDS -> VGPR fragment reads run one MFMA k-step ahead of their use.  LDS
+// reads inside the loop are issued through inline asm with hand-counted
+// s_waitcnt: the compiler would otherwise drain every outstanding
+// global -> LDS copy (vmcnt(0)) before each LDS read, which defeats the ring.
 #include <hip/hip_runtime.h>
+
+#include <utility>
 
 #include "mdnn_internal.h"
 
@@ -33,106 +44,162 @@ namespace mdnn {
 typedef float    f32x16 __attribute__((ext_vector_type(16)));
 typedef float    f32x4  __attribute__((ext_vector_type(4)));
 typedef float    f32x2  __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4  __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2  __attribute__((ext_vector_type(2)));
 
 namespace {
+
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 constexpr uint32_t kOutOfRange = 0xFFFFFFFFu;   // beyond any buffer of < 2^32 bytes
 constexpr int      kRsrcWord3  = 0x00020000;    // raw 32-bit-data buffer descriptor, gfx9 family
 
-__device__ __forceinline__ f32x4 buf_load4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+// ---- compile-time loop (asm immediates must be constants)
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>)
 {
-    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0));
+    (f(std::integral_constant<int, I>{}), ...);
 }
-__device__ __forceinline__ float buf_load1(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f)
 {
-    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, 0));
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// ---- LDS reads the compiler does not see as LDS reads (see header comment)
+template <int OFF> __device__ __forceinline__ void lds_read(float& v, uint32_t addr)
+{
+    asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+}
+template <int OFF> __device__ __forceinline__ void lds_read(f32x2& v, uint32_t addr)
+{
+    asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+}
+template <int OFF> __device__ __forceinline__ void lds_read(f32x4& v, uint32_t addr)
+{
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+}
+__device__ __forceinline__ void lds_read_entry(u32x2& v, uint32_t addr)
+{
+    asm volatile("ds_read_b64 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+}
+// Wait until at most N LDS operations are outstanding.  The registers that the
+// awaited reads fill are threaded through as in/out operands so that nothing
+// that consumes them can be scheduled above the wait.
+template <int N, class T> __device__ __forceinline__ void lds_wait(T& a)
+{
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N));
+}
+template <int N, class T, class U> __device__ __forceinline__ void lds_wait(T& a, U& b)
+{
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+template <int N, class T, class U, class V> __device__ __forceinline__ void lds_wait(T& a, U& b, V& c)
+{
+    asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(a), "+v"(b), "+v"(c) : "n"(N));
+}
+template <int N, class T, class U, class V, class W>
+__device__ __forceinline__ void lds_wait(T& a, U& b, V& c, W& d)
+{
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+}
+template <int N, class T, class U, class V, class W, class X>
+__device__ __forceinline__ void lds_wait(T& a, U& b, V& c, W& d, X& e)
+{
+    asm volatile("s_waitcnt lgkmcnt(%5)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d), "+v"(e) : "n"(N));
+}
+template <int N> __device__ __forceinline__ void vmem_wait()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// Workgroup barrier without the memory fence __syncthreads() carries: the fence
+// would make the compiler drain every outstanding global -> LDS copy here.  The
+// waits that matter are placed by hand around it.
+__device__ __forceinline__ void bare_barrier()
+{
+    asm volatile("s_barrier" ::: "memory");
 }
 
 template <int N> struct VecOf;
 template <> struct VecOf<1> { typedef float type; };
 template <> struct VecOf<2> { typedef f32x2 type; };
 template <> struct VecOf<4> { typedef f32x4 type; };
+__device__ __forceinline__ float comp(const float& v, int) { return v; }
+__device__ __forceinline__ float comp(const f32x2& v, int i) { return v[i]; }
+__device__ __forceinline__ float comp(const f32x4& v, int i) { return v[i]; }
 
 // WO x WM waves per workgroup; each wave owns RA x RB MFMA blocks of 32x32;
-// KS patch columns per pipeline step; VEC = 16-byte global accesses.
-template <int WO_, int WM_, int RA_, int RB_, int KS_, bool VEC_>
+// KS patch columns per slab; NS LDS stages; VW floats per global access (4 or 1).
+template <int WO_, int WM_, int RA_, int RB_, int KS_, int NS_, int VW_>
 struct Cfg {
-    static constexpr int  WO = WO_, WM = WM_, RA = RA_, RB = RB_, KS = KS_;
-    static constexpr bool VEC = VEC_;
-    static constexpr int  NT = 64 * WO * WM;          // threads
-    static constexpr int  TO = WO * RA * 32;          // tile rows (filters)
-    static constexpr int  TM = WM * RB * 32;          // tile columns (flat m)
-    static constexpr int  OG = TO / 4;                // float4 groups per filter-slab row
-    static constexpr int  A_V4 = KS * OG;             // float4s in a filter slab
-    static constexpr int  NA = (A_V4 + NT - 1) / NT;  // filter float4s per thread per slab
-    static constexpr int  MG = TM / 4;                // float4 column groups of the patch slab
-    static constexpr int  BROWS = NT / MG;            // patch rows covered by one pass of the WG
-    static constexpr int  NB = KS / BROWS;            // patch float4s per thread per slab
-    static constexpr int  CS = VEC ? 1 : 4;           // column states per thread
+    static constexpr int WO = WO_, WM = WM_, RA = RA_, RB = RB_, KS = KS_, NS = NS_, VW = VW_;
+    static constexpr int NT = 64 * WO * WM;           // threads
+    static constexpr int TO = WO * RA * 32;           // tile rows (filters)
+    static constexpr int TM = WM * RB * 32;           // tile columns (flat m)
+    static constexpr int OG = TO / VW;                // accesses per filter-slab row
+    static constexpr int A_EL = KS * OG;              // accesses per filter slab
+    static constexpr int NA = (A_EL + NT - 1) / NT;   // filter accesses per thread per slab
+    static constexpr int MG = TM / VW;                // accesses per patch-slab row
+    static constexpr int BROWS = NT / MG;             // patch rows one pass of the workgroup covers
+    static constexpr int NB = KS / BROWS;             // patch accesses per thread per slab
+    static constexpr int NL = NA + NB;                // global -> LDS copies per thread per slab
+    static constexpr int STAGE_FLOATS = KS * (TO + TM);
+    static constexpr uint32_t ring_bytes = (uint32_t)NS * STAGE_FLOATS * sizeof(float);
+    static_assert(VW == 1 || VW == 4, "VW");
     static_assert(NT % MG == 0 && KS % BROWS == 0 && KS % 2 == 0, "tile shape");
+    static_assert(A_EL % 64 == 0, "whole waves only may be masked off in the filter copy");
     static_assert(RB == 1 || RB == 2 || RB == 4, "RB");
-    static constexpr uint32_t stage_bytes = 2u * KS * (TO + TM) * sizeof(float);
+    static_assert(RA >= 1 && RA <= 4, "RA");
+    static_assert(NS >= 2 && (NS - 2) * NL <= 63, "vmcnt range");
 };
 
+// One TO x TM output tile.  `lds` is the workgroup's dynamic LDS: ring, then table.
 template <class C>
-__global__ void __launch_bounds__(C::NT) conv_fprop_kernel(const ConvParams p)
+__device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* lds, const int o0, const int m0)
 {
-    constexpr int WO = C::WO, WM = C::WM, RA = C::RA, RB = C::RB, KS = C::KS;
+    constexpr int WO = C::WO, RA = C::RA, RB = C::RB, KS = C::KS, NS = C::NS, VW = C::VW;
     constexpr int NT = C::NT, TO = C::TO, TM = C::TM, OG = C::OG, MG = C::MG;
-    constexpr int NA = C::NA, NB = C::NB, BROWS = C::BROWS, CS = C::CS;
-    constexpr bool VEC = C::VEC;
-    (void)WM;
+    constexpr int NA = C::NA, NB = C::NB, BROWS = C::BROWS, NL = C::NL;
+    constexpr int STAGE_BYTES = C::STAGE_FLOATS * 4;
+    typedef typename VecOf<RB>::type BVec;
 
-    extern __shared__ __align__(16) unsigned char lds_raw[];
-    float* As  = reinterpret_cast<float*>(lds_raw);          // [2][KS][TO]
-    float* Bs  = As + 2 * KS * TO;                           // [2][KS][TM]
-    int2*  tab = reinterpret_cast<int2*>(Bs + 2 * KS * TM);  // [tab_cap] {byte offset, ky<<16|kx}
-
-    // ---- tile map.  Workgroups are dealt round-robin to the 8 XCDs, each with
-    // its own L2: give every XCD a contiguous run of tiles so that neighbouring
-    // output coordinates (overlapping patches) and the filter tiles of one
-    // coordinate (same patch) meet in the same L2.
-    const int bid  = blockIdx.x;
-    const int tile = (bid & 7) * p.tiles_per_xcd + (bid >> 3);
-    if (tile >= p.n_tiles) return;                           // uniform per workgroup
-    const int mt = tile / p.n_otiles;
-    const int ot = tile - mt * p.n_otiles;
-    const int o0 = ot * TO;
-    const int m0 = mt * TM;
+    u32x2* tab = reinterpret_cast<u32x2*>(lds + C::ring_bytes);   // [tab_cap] {byte offset, ky<<16|kx}
+    const uint32_t lds_base = (uint32_t)(uintptr_t)LDS_PTR(lds);
+    const uint32_t tab_base = lds_base + C::ring_bytes;
 
     const int t    = threadIdx.x;
     const int lane = t & 63;
-    const int wave = t >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wo   = wave % WO;
     const int wm   = wave / WO;
+    const int half = lane >> 5;
+    const int l32  = lane & 31;
 
     const __amdgpu_buffer_rsrc_t rin =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.in), 0, (int)p.in_bytes, kRsrcWord3);
     const __amdgpu_buffer_rsrc_t rfl =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.filt), 0, (int)p.filt_bytes, kRsrcWord3);
 
-    // ---- this thread's patch columns: fixed for the whole tile.
-    const int q    = t % MG;          // float4 column group inside the tile
-    const int brow = t / MG;          // first patch row this thread copies in each pass
-    uint32_t pbase[CS];               // byte offset of the patch origin (+n) in `in`, mod 2^32
-    int      iy0[CS], ix0[CS];        // image row/col of tap (0,0); far negative when the column is past M
-#pragma unroll
-    for (int cs = 0; cs < CS; ++cs) {
-        const int m = m0 + 4 * q + cs;
+    // ---- this thread's patch column group (VW adjacent columns, one output
+    // coordinate because VW divides Nb): fixed for the whole tile.
+    const int q    = t % MG;
+    const int brow = t / MG;
+    uint32_t  pbase;                  // byte offset of the patch origin (+n) in `in`, modulo 2^32
+    int       iy0, ix0;               // image row/col of tap (0,0); far negative when the column is past M
+    {
+        const int m = m0 + VW * q;
         if (m < p.M) {
             const int pix = m / p.Nb;
             const int n   = m - pix * p.Nb;
             const int y   = pix / p.Wo;
             const int x   = pix - y * p.Wo;
-            iy0[cs] = y * p.stride - p.pad;
-            ix0[cs] = x * p.stride - p.pad;
-            // modulo 2^32 on purpose: negative apron origins wrap and wrap back once a valid tap is added
-            pbase[cs] = (((uint32_t)iy0[cs] * (uint32_t)p.Wi + (uint32_t)ix0[cs]) * (uint32_t)p.Nb + (uint32_t)n) * 4u;
+            iy0 = y * p.stride - p.pad;
+            ix0 = x * p.stride - p.pad;
+            // modulo 2^32 on purpose: a negative apron origin wraps, and wraps back once a valid tap is added
+            pbase = (((uint32_t)iy0 * (uint32_t)p.Wi + (uint32_t)ix0) * (uint32_t)p.Nb + (uint32_t)n) * 4u;
         } else {
-            iy0[cs] = -(1 << 30);
-            ix0[cs] = -(1 << 30);
-            pbase[cs] = 0;
+            iy0 = -(1 << 30);
+            ix0 = -(1 << 30);
+            pbase = 0;
         }
     }
 
@@ -144,104 +211,110 @@ __global__ void __launch_bounds__(C::NT) conv_fprop_kernel(const ConvParams p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
-    f32x4 ga[NA], gb[NB];             // global -> LDS staging registers
-
-    // filter slab rows k0..k0+KS-1, columns o0..o0+TO-1 (plain GEMM operand)
-    auto load_A = [&](int k0) {
+    // Copy i of a slab covers accesses e = t + i*NT of the row-major slab, so a
+    // wave's 64 lanes fill 64 consecutive VW-float slots of LDS: exactly what a
+    // global -> LDS load does (LDS address = wave-uniform base + lane * size).
+    // filter slab rows k0..k0+KS-1, columns o0..o0+TO-1: a plain GEMM operand
+    auto issue_A = [&](int k0, int stage) {
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
             const int e = t + i * NT;
+            if ((C::A_EL % NT) != 0 && wave * 64 + i * NT >= C::A_EL) continue;   // wave-uniform
             const int r = e / OG;
             const int c = e - r * OG;
             const int k = k0 + r;
-            const int o = o0 + 4 * c;
-            if ((C::A_V4 % NT) != 0 && e >= C::A_V4) { ga[i] = f32x4{0, 0, 0, 0}; continue; }
-            if (VEC) {
-                const bool ok = (k < p.K) && (o < p.No);
-                ga[i] = buf_load4(rfl, ok ? (uint32_t)(k * p.No + o) * 4u : kOutOfRange);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const bool ok = (k < p.K) && (o + j < p.No);
-                    ga[i][j] = buf_load1(rfl, ok ? (uint32_t)(k * p.No + o + j) * 4u : kOutOfRange);
-                }
-            }
+            const int o = o0 + VW * c;
+            const bool ok = (k < p.K) & (o < p.No);
+            const uint32_t off = ok ? (uint32_t)(k * p.No + o) * 4u : kOutOfRange;
+            unsigned char* dst = lds + stage * STAGE_BYTES + (wave * 64 + i * NT) * (4 * VW);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rfl, LDS_PTR(dst), C::VW * 4, (int)off, 0, 0, 0);
         }
     };
     // patch slab: row k of the unrolled patch for this thread's columns,
     // address = patch base + table[k]; zero when the tap is in the apron.
-    auto load_B = [&](int k0, int kc) {
+    auto issue_B = [&](int k0, int stage, const u32x2 (&ent)[NB]) {
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            const int  k  = k0 + brow + i * BROWS;
-            const int2 e  = tab[k - kc];
-            const int  ky = e.y >> 16;
-            const int  kx = e.y & 0xFFFF;
-#pragma unroll
-            for (int cs = 0; cs < CS; ++cs) {
-                const bool ok = (k < p.K) && ((uint32_t)(iy0[cs] + ky) < (uint32_t)p.Hi) &&
-                                ((uint32_t)(ix0[cs] + kx) < (uint32_t)p.Wi);
-                const uint32_t off = ok ? pbase[cs] + (uint32_t)e.x : kOutOfRange;
-                if (VEC) gb[i] = buf_load4(rin, off);
-                else     gb[i][cs] = buf_load1(rin, off);
-            }
+            const int k  = k0 + brow + i * BROWS;
+            const int ky = (int)ent[i].y >> 16;
+            const int kx = (int)(ent[i].y & 0xFFFFu);
+            const bool ok = (k < p.K) & ((uint32_t)(iy0 + ky) < (uint32_t)p.Hi) &
+                            ((uint32_t)(ix0 + kx) < (uint32_t)p.Wi);
+            const uint32_t off = ok ? pbase + ent[i].x : kOutOfRange;
+            unsigned char* dst = lds + stage * STAGE_BYTES + KS * TO * 4 + (wave * 64 + i * NT) * (4 * VW);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rin, LDS_PTR(dst), C::VW * 4, (int)off, 0, 0, 0);
         }
     };
-    auto store_AB = [&](int stage) {
-        float* as = As + stage * KS * TO;
-        float* bs = Bs + stage * KS * TM;
+    // table entries of the rows this thread copies in the slab at table index ti0
+    auto read_entries = [&](int ti0, u32x2 (&ent)[NB]) {
 #pragma unroll
-        for (int i = 0; i < NA; ++i) {
-            const int e = t + i * NT;
-            if ((C::A_V4 % NT) != 0 && e >= C::A_V4) continue;
-            *reinterpret_cast<f32x4*>(as + 4 * e) = ga[i];          // row-major [KS][TO], e*4 == r*TO + 4c
-        }
-#pragma unroll
-        for (int i = 0; i < NB; ++i)
-            *reinterpret_cast<f32x4*>(bs + (brow + i * BROWS) * TM + 4 * q) = gb[i];
+        for (int i = 0; i < NB; ++i) lds_read_entry(ent[i], tab_base + (uint32_t)(ti0 + brow + i * BROWS) * 8u);
+    };
+    auto wait_entries = [&](u32x2 (&ent)[NB]) {
+        if constexpr (NB == 1) lds_wait<0>(ent[0]);
+        else if constexpr (NB == 2) lds_wait<0>(ent[0], ent[1]);
+        else if constexpr (NB == 4) lds_wait<0>(ent[0], ent[1], ent[2], ent[3]);
+        else static_assert(NB == 1 || NB == 2 || NB == 4, "NB");
     };
 
     // One slab on the matrix cores.  MFMA 32x32x2: lane l supplies A[l%32][l/32]
     // and B[l/32][l%32]; rows = filters, columns = flat m.  Column block b of a
     // wave holds m = base + RB*(l%32) + b, so one RB-wide LDS read feeds all RB
     // column blocks and the RB results of a lane are adjacent in memory.
-    const int half = lane >> 5;
-    const int l32  = lane & 31;
+    // Fragments for k-step j+1 are requested before the MFMAs of k-step j.
+    const uint32_t a_lane = (uint32_t)(half * TO + wo * (RA * 32) + l32) * 4u;
+    const uint32_t b_lane = (uint32_t)(KS * TO + half * TM + wm * (RB * 32) + l32 * RB) * 4u;
     auto compute = [&](int stage) {
-        const float* as = As + stage * KS * TO + half * TO + wo * (RA * 32) + l32;
-        const float* bs = Bs + stage * KS * TM + half * TM + wm * (RB * 32) + l32 * RB;
-#pragma unroll
-        for (int kk = 0; kk < KS; kk += 2) {
-            float av[RA];
-            typename VecOf<RB>::type bv;
-#pragma unroll
-            for (int a = 0; a < RA; ++a) av[a] = as[kk * TO + a * 32];
-            bv = *reinterpret_cast<const typename VecOf<RB>::type*>(bs + kk * TM);
+        const uint32_t a_addr = lds_base + stage * STAGE_BYTES + a_lane;
+        const uint32_t b_addr = lds_base + stage * STAGE_BYTES + b_lane;
+        float av[2][RA];
+        BVec  bv[2];
+        auto request = [&](auto jc, auto bufc) {
+            constexpr int j = decltype(jc)::value, buf = decltype(bufc)::value;
+            static_for<RA>([&](auto ac) {
+                constexpr int a = decltype(ac)::value;
+                lds_read<(2 * j * TO + a * 32) * 4>(av[buf][a], a_addr);
+            });
+            lds_read<2 * j * TM * 4>(bv[buf], b_addr);
+        };
+        auto await = [&](auto pendc, auto bufc) {
+            constexpr int pend = decltype(pendc)::value, buf = decltype(bufc)::value;
+            if constexpr (RA == 1) lds_wait<pend>(av[buf][0], bv[buf]);
+            else if constexpr (RA == 2) lds_wait<pend>(av[buf][0], av[buf][1], bv[buf]);
+            else if constexpr (RA == 3) lds_wait<pend>(av[buf][0], av[buf][1], av[buf][2], bv[buf]);
+            else lds_wait<pend>(av[buf][0], av[buf][1], av[buf][2], av[buf][3], bv[buf]);
+        };
+        request(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        static_for<KS / 2>([&](auto jc) {
+            constexpr int j = decltype(jc)::value, cur = j & 1;
+            if constexpr (j + 1 < KS / 2) {
+                request(std::integral_constant<int, j + 1>{}, std::integral_constant<int, cur ^ 1>{});
+                await(std::integral_constant<int, RA + 1>{}, std::integral_constant<int, cur>{});
+            } else {
+                await(std::integral_constant<int, 0>{}, std::integral_constant<int, cur>{});
+            }
 #pragma unroll
             for (int a = 0; a < RA; ++a)
 #pragma unroll
-                for (int b = 0; b < RB; ++b) {
-                    float bval;
-                    if constexpr (RB == 1) bval = bv; else bval = bv[b];
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[a], bval, acc[a][b], 0, 0, 0);
-                }
-        }
+                for (int b = 0; b < RB; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][a], comp(bv[cur], b), acc[a][b], 0, 0, 0);
+        });
     };
 
     // ---- main loop over K, in table-sized chunks (one chunk unless K is huge)
     for (int kc = 0; kc < p.K; kc += p.tab_cap) {
-        if (kc) __syncthreads();
+        __syncthreads();              // previous tile / chunk has let go of the ring and the table
         // offset table, Section 3.2: k = (c*Sk + ky)*Sk + kx  ->  ((c*Hi + ky)*Wi + kx)*Nb floats
         for (int i = t; i < p.tab_cap; i += NT) {
             const int k = kc + i;
-            int2 e = make_int2(0, 0);
+            u32x2 e = {0u, 0u};
             if (k < p.K) {
                 const int c  = k / p.SkSk;
                 const int r  = k - c * p.SkSk;
                 const int ky = r / p.Sk;
                 const int kx = r - ky * p.Sk;
-                e.x = (int)((uint32_t)((c * p.Hi + ky) * p.Wi + kx) * (uint32_t)p.Nb * 4u);
-                e.y = (ky << 16) | kx;
+                e.x = (uint32_t)((c * p.Hi + ky) * p.Wi + kx) * (uint32_t)p.Nb * 4u;
+                e.y = ((uint32_t)ky << 16) | (uint32_t)kx;
             }
             tab[i] = e;
         }
@@ -249,19 +322,39 @@ __global__ void __launch_bounds__(C::NT) conv_fprop_kernel(const ConvParams p)
 
         const int kend = min(p.K, kc + p.tab_cap);
         const int ns   = (kend - kc + KS - 1) / KS;
-        load_A(kc);
-        load_B(kc, kc);
-        store_AB(0);
-        __syncthreads();
-        for (int s = 0; s < ns; ++s) {
-            const bool more = (s + 1 < ns);
-            if (more) {                           // next slab's global loads fly during the MFMAs
-                load_A(kc + (s + 1) * KS);
-                load_B(kc + (s + 1) * KS, kc);
+        u32x2 ent[NB];
+
+        // prologue: slabs 0 .. NS-2 in flight, entries of slab NS-1 requested
+#pragma unroll
+        for (int s = 0; s < NS - 1; ++s) {
+            if (s < ns) {
+                read_entries(s * KS, ent);
+                wait_entries(ent);
+                issue_A(kc + s * KS, s);
+                issue_B(kc + s * KS, s, ent);
             }
-            compute(s & 1);
-            if (more) store_AB((s + 1) & 1);      // other stage: last read one barrier ago
-            __syncthreads();
+        }
+        if (NS - 1 < ns) read_entries((NS - 1) * KS, ent);
+
+        int stage = 0;                // s % NS
+        for (int s = 0; s < ns; ++s) {
+            // this wave's share of slab s has landed once at most min(NS-2, ns-1-s) younger slabs are in flight
+            const int younger = min(NS - 2, ns - 1 - s);
+            static_for<NS - 1>([&](auto yc) {
+                constexpr int y = decltype(yc)::value;
+                if (younger == y) vmem_wait<y * NL>();
+            });
+            bare_barrier();           // everyone's share landed; everyone is done with slab s-1
+            if (s + NS - 1 < ns) {    // refill the stage slab s-1 just left
+                int st = stage + NS - 1;
+                if (st >= NS) st -= NS;
+                wait_entries(ent);
+                issue_A(kc + (s + NS - 1) * KS, st);
+                issue_B(kc + (s + NS - 1) * KS, st, ent);
+                if (s + NS < ns) read_entries((s + NS) * KS, ent);
+            }
+            compute(stage);
+            if (++stage == NS) stage = 0;
         }
     }
 
@@ -275,15 +368,15 @@ __global__ void __launch_bounds__(C::NT) conv_fprop_kernel(const ConvParams p)
             const int o = o0 + wo * (RA * 32) + a * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
             if (o >= p.No) continue;
             float* dst = p.out + (size_t)o * (size_t)p.M + ocol;
-            if (VEC) {
+            if constexpr (VW == 4) {
                 if (ocol < p.M) {                 // M % 4 == 0 and RB | 4: all or nothing
-                    typename VecOf<RB>::type w;
+                    BVec w;
 #pragma unroll
                     for (int b = 0; b < RB; ++b) {
                         if constexpr (RB == 1) w = p.alpha * acc[a][0][v];
                         else w[b] = p.alpha * acc[a][b][v];
                     }
-                    *reinterpret_cast<typename VecOf<RB>::type*>(dst) = w;
+                    *reinterpret_cast<BVec*>(dst) = w;
                 }
             } else {
 #pragma unroll
@@ -292,6 +385,22 @@ __global__ void __launch_bounds__(C::NT) conv_fprop_kernel(const ConvParams p)
             }
         }
     }
+}
+
+template <class C>
+__global__ void __launch_bounds__(C::NT) conv_fprop_kernel(const ConvParams p)
+{
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    // ---- tile map.  Workgroups are dealt round-robin to the 8 XCDs, each with
+    // its own L2: give every XCD a contiguous run of tiles so that neighbouring
+    // output coordinates (overlapping patches) and the filter tiles of one
+    // coordinate (same patch) meet in the same L2.
+    const int bid  = blockIdx.x;
+    const int tile = (bid & 7) * p.tiles_per_xcd + (bid >> 3);
+    if (tile >= p.n_tiles) return;                           // uniform per workgroup
+    const int mt = tile / p.n_otiles;
+    const int ot = tile - mt * p.n_otiles;
+    conv_tile<C>(p, lds_raw, ot * C::TO, mt * C::TM);
 }
 
 // ---- register-only FP32 MFMA loop: the sustained matrix rate with no memory traffic
@@ -320,32 +429,32 @@ typedef void (*KernelFn)(const ConvParams);
 struct Entry {
     VariantInfo info;
     KernelFn    fn;
-    uint32_t    stage_bytes;
+    uint32_t    ring_bytes;
 };
 
 template <class C>
 constexpr Entry make_entry(const char* name, int wg_per_cu, float eff)
 {
-    return Entry{VariantInfo{name, C::TO, C::TM, C::KS, C::NT, C::VEC ? 1 : 0, wg_per_cu, eff},
-                 &conv_fprop_kernel<C>, C::stage_bytes};
+    return Entry{VariantInfo{name, C::TO, C::TM, C::KS, C::NT, C::VW == 4 ? 1 : 0, wg_per_cu, eff},
+                 &conv_fprop_kernel<C>, C::ring_bytes};
 }
 
-//                         WO WM RA RB KS  VEC
-typedef Cfg<2, 2, 2, 2, 16, true>  C_o128m128;
-typedef Cfg<2, 2, 4, 2, 16, true>  C_o256m128;
-typedef Cfg<2, 2, 2, 4, 16, true>  C_o128m256;
-typedef Cfg<1, 4, 3, 2, 16, true>  C_o96m256;
-typedef Cfg<1, 4, 2, 2, 16, true>  C_o64m256;
-typedef Cfg<1, 4, 1, 1, 16, true>  C_o32m128;
-typedef Cfg<2, 2, 1, 1, 16, false> C_o64m64s;
+//          WO WM RA RB KS NS VW
+typedef Cfg<2, 2, 2, 2, 16, 3, 4> C_o128m128;
+typedef Cfg<2, 2, 4, 2, 16, 3, 4> C_o256m128;
+typedef Cfg<2, 2, 2, 4, 16, 3, 4> C_o128m256;
+typedef Cfg<1, 4, 3, 2, 16, 3, 4> C_o96m256;
+typedef Cfg<1, 4, 2, 2, 16, 3, 4> C_o64m256;
+typedef Cfg<1, 4, 1, 1, 16, 3, 4> C_o32m128;
+typedef Cfg<2, 2, 1, 1, 16, 3, 1> C_o64m64s;
 
 const Entry kEntries[] = {
     make_entry<C_o128m128>("o128m128", 2, 0.85f),
-    make_entry<C_o256m128>("o256m128", 2, 0.88f),
-    make_entry<C_o128m256>("o128m256", 2, 0.88f),
-    make_entry<C_o96m256>("o96m256", 2, 0.85f),
-    make_entry<C_o64m256>("o64m256", 2, 0.80f),
-    make_entry<C_o32m128>("o32m128", 4, 0.50f),
+    make_entry<C_o256m128>("o256m128", 1, 0.80f),
+    make_entry<C_o128m256>("o128m256", 1, 0.80f),
+    make_entry<C_o96m256>("o96m256", 2, 0.80f),
+    make_entry<C_o64m256>("o64m256", 2, 0.78f),
+    make_entry<C_o32m128>("o32m128", 4, 0.70f),
     make_entry<C_o64m64s>("o64m64s", 4, 0.30f),
 };
 constexpr int kNumEntries = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
@@ -356,7 +465,7 @@ int variant_count() { return kNumEntries; }
 const VariantInfo& variant_info(int i) { return kEntries[i].info; }
 uint32_t variant_lds_bytes(int i, int tab_cap)
 {
-    return kEntries[i].stage_bytes + (uint32_t)tab_cap * (uint32_t)sizeof(int2);
+    return kEntries[i].ring_bytes + (uint32_t)tab_cap * 8u;
 }
 
 int launch_variant(int i, const ConvParams& p, void* stream)
