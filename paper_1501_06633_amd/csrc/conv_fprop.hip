@@ -257,49 +257,44 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
         else static_assert(NB == 1 || NB == 2 || NB == 4, "NB");
     };
 
-    // One slab on the matrix cores.  MFMA 32x32x2: lane l supplies A[l%32][l/32]
-    // and B[l/32][l%32]; rows = filters, columns = flat m.  Column block b of a
-    // wave holds m = base + RB*(l%32) + b, so one RB-wide LDS read feeds all RB
-    // column blocks and the RB results of a lane are adjacent in memory.
-    // Fragments for k-step j+1 are requested before the MFMAs of k-step j.
+    // The matrix-core loop.  MFMA 32x32x2: lane l supplies A[l%32][l/32] and
+    // B[l/32][l%32]; rows = filters, columns = flat m.  Column block b of a wave
+    // holds m = base + RB*(l%32) + b, so one RB-wide LDS read feeds all RB column
+    // blocks and the RB results of a lane are adjacent in memory.
+    //
+    // Schedule.  Slab s lives in stage s % NS.  The fragments of k-step j+1 are
+    // requested from LDS before the MFMAs of k-step j issue, across slab
+    // boundaries too, so the MFMA stream never waits on LDS latency.  The one
+    // barrier per slab sits inside slab s, before k-step JB: by then every wave
+    // has waited for its own share of slab s+1, so after the barrier slab s+1 is
+    // complete and visible, and every wave is done with slab s-1, whose stage is
+    // refilled with slab s+NS-1; the refill's address arithmetic and loads are
+    // issued in between that k-step's MFMAs.
+    constexpr int NSTEP = KS / 2;     // MFMA k-steps per slab
+    constexpr int JB    = 1;          // k-step in front of which the barrier sits
+    constexpr int NM    = RA * RB;    // MFMAs per k-step
+    static_assert(NSTEP % 2 == 0 && JB < NSTEP, "fragment double-buffer parity must not depend on the slab");
     const uint32_t a_lane = (uint32_t)(half * TO + wo * (RA * 32) + l32) * 4u;
     const uint32_t b_lane = (uint32_t)(KS * TO + half * TM + wm * (RB * 32) + l32 * RB) * 4u;
-    auto compute = [&](int stage) {
-        const uint32_t a_addr = lds_base + stage * STAGE_BYTES + a_lane;
-        const uint32_t b_addr = lds_base + stage * STAGE_BYTES + b_lane;
-        float av[2][RA];
-        BVec  bv[2];
-        auto request = [&](auto jc, auto bufc) {
-            constexpr int j = decltype(jc)::value, buf = decltype(bufc)::value;
-            static_for<RA>([&](auto ac) {
-                constexpr int a = decltype(ac)::value;
-                lds_read<(2 * j * TO + a * 32) * 4>(av[buf][a], a_addr);
-            });
-            lds_read<2 * j * TM * 4>(bv[buf], b_addr);
-        };
-        auto await = [&](auto pendc, auto bufc) {
-            constexpr int pend = decltype(pendc)::value, buf = decltype(bufc)::value;
-            if constexpr (RA == 1) lds_wait<pend>(av[buf][0], bv[buf]);
-            else if constexpr (RA == 2) lds_wait<pend>(av[buf][0], av[buf][1], bv[buf]);
-            else if constexpr (RA == 3) lds_wait<pend>(av[buf][0], av[buf][1], av[buf][2], bv[buf]);
-            else lds_wait<pend>(av[buf][0], av[buf][1], av[buf][2], av[buf][3], bv[buf]);
-        };
-        request(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-        static_for<KS / 2>([&](auto jc) {
-            constexpr int j = decltype(jc)::value, cur = j & 1;
-            if constexpr (j + 1 < KS / 2) {
-                request(std::integral_constant<int, j + 1>{}, std::integral_constant<int, cur ^ 1>{});
-                await(std::integral_constant<int, RA + 1>{}, std::integral_constant<int, cur>{});
-            } else {
-                await(std::integral_constant<int, 0>{}, std::integral_constant<int, cur>{});
-            }
-#pragma unroll
-            for (int a = 0; a < RA; ++a)
-#pragma unroll
-                for (int b = 0; b < RB; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][a], comp(bv[cur], b), acc[a][b], 0, 0, 0);
+    float av[2][RA];
+    BVec  bv[2];
+    auto request = [&](auto jc, auto bufc, uint32_t a_addr, uint32_t b_addr) {
+        constexpr int j = decltype(jc)::value, buf = decltype(bufc)::value;
+        static_for<RA>([&](auto ac) {
+            constexpr int a = decltype(ac)::value;
+            lds_read<(2 * j * TO + a * 32) * 4>(av[buf][a], a_addr);
         });
+        lds_read<2 * j * TM * 4>(bv[buf], b_addr);
     };
+    auto await = [&](auto pendc, auto bufc) {
+        constexpr int pend = decltype(pendc)::value, buf = decltype(bufc)::value;
+        if constexpr (RA == 1) lds_wait<pend>(av[buf][0], bv[buf]);
+        else if constexpr (RA == 2) lds_wait<pend>(av[buf][0], av[buf][1], bv[buf]);
+        else if constexpr (RA == 3) lds_wait<pend>(av[buf][0], av[buf][1], av[buf][2], bv[buf]);
+        else lds_wait<pend>(av[buf][0], av[buf][1], av[buf][2], av[buf][3], bv[buf]);
+    };
+    typedef std::integral_constant<int, 0> I0;
+    typedef std::integral_constant<int, 1> I1;
 
     // ---- main loop over K, in table-sized chunks (one chunk unless K is huge)
     for (int kc = 0; kc < p.K; kc += p.tab_cap) {
@@ -324,7 +319,8 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
         const int ns   = (kend - kc + KS - 1) / KS;
         u32x2 ent[NB];
 
-        // prologue: slabs 0 .. NS-2 in flight, entries of slab NS-1 requested
+        // prologue: slabs 0 .. NS-2 in flight, entries of slab NS-1 requested,
+        // slab 0 complete and visible, its first fragments requested
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s) {
             if (s < ns) {
@@ -335,26 +331,79 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
             }
         }
         if (NS - 1 < ns) read_entries((NS - 1) * KS, ent);
-
-        int stage = 0;                // s % NS
-        for (int s = 0; s < ns; ++s) {
-            // this wave's share of slab s has landed once at most min(NS-2, ns-1-s) younger slabs are in flight
-            const int younger = min(NS - 2, ns - 1 - s);
+        {
+            const int younger = min(NS - 2, ns - 1);
             static_for<NS - 1>([&](auto yc) {
                 constexpr int y = decltype(yc)::value;
                 if (younger == y) vmem_wait<y * NL>();
             });
-            bare_barrier();           // everyone's share landed; everyone is done with slab s-1
-            if (s + NS - 1 < ns) {    // refill the stage slab s-1 just left
-                int st = stage + NS - 1;
-                if (st >= NS) st -= NS;
-                wait_entries(ent);
-                issue_A(kc + (s + NS - 1) * KS, st);
-                issue_B(kc + (s + NS - 1) * KS, st, ent);
-                if (s + NS < ns) read_entries((s + NS) * KS, ent);
-            }
-            compute(stage);
-            if (++stage == NS) stage = 0;
+        }
+        bare_barrier();
+        request(I0{}, I0{}, lds_base + a_lane, lds_base + b_lane);
+
+        int stage = 0;                // s % NS
+        for (int s = 0; s < ns; ++s) {
+            const int      nstage   = (stage + 1 == NS) ? 0 : stage + 1;
+            const uint32_t a_addr   = lds_base + stage * STAGE_BYTES + a_lane;
+            const uint32_t b_addr   = lds_base + stage * STAGE_BYTES + b_lane;
+            const uint32_t a_next   = lds_base + nstage * STAGE_BYTES + a_lane;
+            const uint32_t b_next   = lds_base + nstage * STAGE_BYTES + b_lane;
+            const bool     has_next = (s + 1 < ns);
+            const bool     refill   = (s + NS - 1 < ns);
+            int rstage = stage + NS - 1;          // (s + NS - 1) % NS
+            if (rstage >= NS) rstage -= NS;
+
+            static_for<NSTEP>([&](auto jc) {
+                constexpr int j = decltype(jc)::value, cur = j & 1;
+                if constexpr (j == JB) {
+                    if (has_next) {
+                        // own share of slab s+1 landed: slabs s+2 .. s+NS-2 may still be in flight
+                        const int younger = min(NS - 3, ns - 2 - s);
+                        static_for<(NS > 2 ? NS - 2 : 1)>([&](auto yc) {
+                            constexpr int y = decltype(yc)::value;
+                            if (younger == y) vmem_wait<y * NL>();
+                        });
+                        bare_barrier();
+                    }
+                }
+                if constexpr (j + 1 < NSTEP) {
+                    request(std::integral_constant<int, j + 1>{}, std::integral_constant<int, cur ^ 1>{}, a_addr, b_addr);
+                    await(std::integral_constant<int, RA + 1>{}, std::integral_constant<int, cur>{});
+                } else {
+                    if (has_next) {
+                        request(I0{}, std::integral_constant<int, cur ^ 1>{}, a_next, b_next);
+                        await(std::integral_constant<int, RA + 1>{}, std::integral_constant<int, cur>{});
+                    } else {
+                        await(I0{}, std::integral_constant<int, cur>{});
+                    }
+                }
+                static_for<NM>([&](auto mc) {
+                    constexpr int mi = decltype(mc)::value, a = mi / RB, b = mi % RB;
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][a], comp(bv[cur], b), acc[a][b], 0, 0, 0);
+                    if constexpr (j == JB) {
+                        // refill, spread behind the MFMAs of this k-step so that its issue slots are free ones
+                        if constexpr (mi == 0) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (refill) {
+                                wait_entries(ent);
+                                issue_A(kc + (s + NS - 1) * KS, rstage);
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        if constexpr (mi == (NM > 1 ? 1 : 0)) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (refill) issue_B(kc + (s + NS - 1) * KS, rstage, ent);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        if constexpr (mi == (NM > 2 ? 2 : NM - 1)) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (s + NS < ns) read_entries((s + NS) * KS, ent);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
+                });
+            });
+            stage = nstage;
         }
     }
 
