@@ -78,9 +78,9 @@ template <int OFF> __device__ __forceinline__ void lds_read(f32x4& v, uint32_t a
 {
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
 }
-__device__ __forceinline__ void lds_read_entry(u32x2& v, uint32_t addr)
+template <int OFF> __device__ __forceinline__ void lds_read(u32x2& v, uint32_t addr)
 {
-    asm volatile("ds_read_b64 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+    asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
 }
 // Wait until at most N LDS operations are outstanding.  The registers that the
 // awaited reads fill are threaded through as in/out operands so that nothing
@@ -123,9 +123,11 @@ template <int N> struct VecOf;
 template <> struct VecOf<1> { typedef float type; };
 template <> struct VecOf<2> { typedef f32x2 type; };
 template <> struct VecOf<4> { typedef f32x4 type; };
-__device__ __forceinline__ float comp(const float& v, int) { return v; }
-__device__ __forceinline__ float comp(const f32x2& v, int i) { return v[i]; }
-__device__ __forceinline__ float comp(const f32x4& v, int i) { return v[i]; }
+template <class V> __device__ __forceinline__ float comp(const V& v, int i)
+{
+    if constexpr (sizeof(V) == sizeof(float)) return v;
+    else return v[i];
+}
 
 // WO x WM waves per workgroup; each wave owns RA x RB MFMA blocks of 32x32;
 // KS patch columns per slab; NS LDS stages; VW floats per global access (4 or 1).
@@ -160,6 +162,7 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
     constexpr int NT = C::NT, TO = C::TO, TM = C::TM, OG = C::OG, MG = C::MG;
     constexpr int NA = C::NA, NB = C::NB, BROWS = C::BROWS, NL = C::NL;
     constexpr int STAGE_BYTES = C::STAGE_FLOATS * 4;
+    constexpr int ACCESS = 4 * VW;    // bytes per lane per global -> LDS copy
     typedef typename VecOf<RB>::type BVec;
 
     u32x2* tab = reinterpret_cast<u32x2*>(lds + C::ring_bytes);   // [tab_cap] {byte offset, ky<<16|kx}
@@ -185,6 +188,7 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
     const int brow = t / MG;
     uint32_t  pbase;                  // byte offset of the patch origin (+n) in `in`, modulo 2^32
     int       iy0, ix0;               // image row/col of tap (0,0); far negative when the column is past M
+    bool      col_inside;             // every tap of this column's patch lies inside the image
     {
         const int m = m0 + VW * q;
         if (m < p.M) {
@@ -196,11 +200,27 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
             ix0 = x * p.stride - p.pad;
             // modulo 2^32 on purpose: a negative apron origin wraps, and wraps back once a valid tap is added
             pbase = (((uint32_t)iy0 * (uint32_t)p.Wi + (uint32_t)ix0) * (uint32_t)p.Nb + (uint32_t)n) * 4u;
+            col_inside = (iy0 >= 0) & (iy0 + p.Sk <= p.Hi) & (ix0 >= 0) & (ix0 + p.Sk <= p.Wi);
         } else {
             iy0 = -(1 << 30);
             ix0 = -(1 << 30);
             pbase = 0;
+            col_inside = false;
         }
+    }
+    // Tiles whose patches never touch the apron (most of them) take a loop
+    // without the per-tap boundary test.  Workgroup-wide AND through LDS.
+    bool interior;
+    {
+        uint32_t* flags = reinterpret_cast<uint32_t*>(lds);
+        __syncthreads();              // previous tile has let go of LDS
+        const bool wave_inside = (__builtin_amdgcn_ballot_w64(col_inside) == __builtin_amdgcn_ballot_w64(true));
+        if (lane == 0) flags[wave] = wave_inside ? 1u : 0u;
+        __syncthreads();
+        uint32_t all = 1u;
+#pragma unroll
+        for (int w = 0; w < NT / 64; ++w) all &= flags[w];
+        interior = (__builtin_amdgcn_readfirstlane(all) != 0);
     }
 
     f32x16 acc[RA][RB];
@@ -211,44 +231,66 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
-    // Copy i of a slab covers accesses e = t + i*NT of the row-major slab, so a
-    // wave's 64 lanes fill 64 consecutive VW-float slots of LDS: exactly what a
-    // global -> LDS load does (LDS address = wave-uniform base + lane * size).
-    // filter slab rows k0..k0+KS-1, columns o0..o0+TO-1: a plain GEMM operand
-    auto issue_A = [&](int k0, int stage) {
+    // ---- global -> LDS copies.  Copy i of a slab covers accesses e = t + i*NT
+    // of the row-major slab, so a wave's 64 lanes fill 64 consecutive slots of
+    // LDS: what a global -> LDS load does (LDS address = wave-uniform base +
+    // lane * size).  Every instruction issued inside the MFMA loop costs matrix
+    // issue slots, so the per-slab address work is one add per copy.
+    //
+    // Filter slab: rows k0..k0+KS-1, columns o0..o0+TO-1 of the K x No matrix.
+    // No predicate: a row k >= K lies beyond the end of the buffer and reads as
+    // 0 (which also silences whatever the patch slab holds in that row), and a
+    // column o >= No only feeds output rows that are never stored.
+    uint32_t voffA[NA];
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int e = t + i * NT;
+        const int r = e / OG;
+        const int c = e - r * OG;
+        voffA[i] = ((uint32_t)r * (uint32_t)p.No + (uint32_t)(o0 + VW * c)) * 4u;
+    }
+    const uint32_t strideA = (uint32_t)KS * (uint32_t)p.No * 4u;
+    unsigned char* const dma_base = lds + wave * (64 * ACCESS);               // wave-uniform
+    auto issue_A = [&](auto stc) {
+        constexpr int st = decltype(stc)::value;
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
-            const int e = t + i * NT;
             if ((C::A_EL % NT) != 0 && wave * 64 + i * NT >= C::A_EL) continue;   // wave-uniform
-            const int r = e / OG;
-            const int c = e - r * OG;
-            const int k = k0 + r;
-            const int o = o0 + VW * c;
-            const bool ok = (k < p.K) & (o < p.No);
-            const uint32_t off = ok ? (uint32_t)(k * p.No + o) * 4u : kOutOfRange;
-            unsigned char* dst = lds + stage * STAGE_BYTES + (wave * 64 + i * NT) * (4 * VW);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rfl, LDS_PTR(dst), C::VW * 4, (int)off, 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rfl, LDS_PTR(dma_base + (st * STAGE_BYTES + i * NT * ACCESS)), C::VW * 4,
+                (int)voffA[i], 0, 0, 0);
+            voffA[i] += strideA;
         }
     };
-    // patch slab: row k of the unrolled patch for this thread's columns,
-    // address = patch base + table[k]; zero when the tap is in the apron.
-    auto issue_B = [&](int k0, int stage, const u32x2 (&ent)[NB]) {
+    // Patch slab: row k of the unrolled patch for this thread's columns, address
+    // = patch base + table[k]; a tap in the apron gets an out-of-range offset
+    // and reads as 0.  Table rows k >= K hold offset 0: they fetch finite data
+    // (or 0) that meets a zero filter row.
+    auto issue_B = [&](auto stc, auto insidec, const u32x2 (&ent)[NB]) {
+        constexpr int  st     = decltype(stc)::value;
+        constexpr bool inside = decltype(insidec)::value;
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            const int k  = k0 + brow + i * BROWS;
-            const int ky = (int)ent[i].y >> 16;
-            const int kx = (int)(ent[i].y & 0xFFFFu);
-            const bool ok = (k < p.K) & ((uint32_t)(iy0 + ky) < (uint32_t)p.Hi) &
-                            ((uint32_t)(ix0 + kx) < (uint32_t)p.Wi);
-            const uint32_t off = ok ? pbase + ent[i].x : kOutOfRange;
-            unsigned char* dst = lds + stage * STAGE_BYTES + KS * TO * 4 + (wave * 64 + i * NT) * (4 * VW);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rin, LDS_PTR(dst), C::VW * 4, (int)off, 0, 0, 0);
+            uint32_t off = pbase + ent[i].x;
+            if constexpr (!inside) {
+                const int  ky = (int)ent[i].y >> 16;
+                const int  kx = (int)(ent[i].y & 0xFFFFu);
+                const bool ok = ((uint32_t)(iy0 + ky) < (uint32_t)p.Hi) & ((uint32_t)(ix0 + kx) < (uint32_t)p.Wi);
+                off = ok ? off : kOutOfRange;
+            }
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rin, LDS_PTR(dma_base + (st * STAGE_BYTES + KS * TO * 4 + i * NT * ACCESS)), C::VW * 4,
+                (int)off, 0, 0, 0);
         }
     };
-    // table entries of the rows this thread copies in the slab at table index ti0
-    auto read_entries = [&](int ti0, u32x2 (&ent)[NB]) {
-#pragma unroll
-        for (int i = 0; i < NB; ++i) lds_read_entry(ent[i], tab_base + (uint32_t)(ti0 + brow + i * BROWS) * 8u);
+    // table entries of the rows this thread copies, slab after slab
+    uint32_t ent_addr = tab_base + (uint32_t)brow * 8u;
+    auto read_entries = [&](u32x2 (&ent)[NB]) {
+        static_for<NB>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            lds_read<i * BROWS * 8>(ent[i], ent_addr);
+        });
+        ent_addr += KS * 8;
     };
     auto wait_entries = [&](u32x2 (&ent)[NB]) {
         if constexpr (NB == 1) lds_wait<0>(ent[0]);
@@ -257,34 +299,37 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
         else static_assert(NB == 1 || NB == 2 || NB == 4, "NB");
     };
 
-    // The matrix-core loop.  MFMA 32x32x2: lane l supplies A[l%32][l/32] and
-    // B[l/32][l%32]; rows = filters, columns = flat m.  Column block b of a wave
-    // holds m = base + RB*(l%32) + b, so one RB-wide LDS read feeds all RB column
-    // blocks and the RB results of a lane are adjacent in memory.
+    // ---- the matrix-core loop.  MFMA 32x32x2: lane l supplies A[l%32][l/32]
+    // and B[l/32][l%32]; rows = filters, columns = flat m.  Column block b of a
+    // wave holds m = base + RB*(l%32) + b, so one RB-wide LDS read feeds all RB
+    // column blocks and the RB results of a lane are adjacent in memory.
     //
-    // Schedule.  Slab s lives in stage s % NS.  The fragments of k-step j+1 are
-    // requested from LDS before the MFMAs of k-step j issue, across slab
-    // boundaries too, so the MFMA stream never waits on LDS latency.  The one
-    // barrier per slab sits inside slab s, before k-step JB: by then every wave
-    // has waited for its own share of slab s+1, so after the barrier slab s+1 is
-    // complete and visible, and every wave is done with slab s-1, whose stage is
-    // refilled with slab s+NS-1; the refill's address arithmetic and loads are
-    // issued in between that k-step's MFMAs.
+    // Schedule.  Slab s lives in stage s % NS; the slab loop is unrolled NS
+    // times so that every LDS address is a constant offset from one register.
+    // The fragments of k-step j+1 are requested from LDS before the MFMAs of
+    // k-step j issue, across slab boundaries too, so the MFMA stream never waits
+    // on LDS latency.  The one barrier per slab sits inside slab s, before
+    // k-step JB: by then every wave has waited for its own share of slab s+1,
+    // so after the barrier slab s+1 is complete and visible, and every wave is
+    // done with slab s-1, whose stage is refilled with slab s+NS-1; the refill
+    // is issued in between that k-step's MFMAs.
     constexpr int NSTEP = KS / 2;     // MFMA k-steps per slab
     constexpr int JB    = 1;          // k-step in front of which the barrier sits
     constexpr int NM    = RA * RB;    // MFMAs per k-step
     static_assert(NSTEP % 2 == 0 && JB < NSTEP, "fragment double-buffer parity must not depend on the slab");
-    const uint32_t a_lane = (uint32_t)(half * TO + wo * (RA * 32) + l32) * 4u;
-    const uint32_t b_lane = (uint32_t)(KS * TO + half * TM + wm * (RB * 32) + l32 * RB) * 4u;
+    static_assert((NS - 1) * STAGE_BYTES + (2 * (NSTEP - 1) * TO + (RA - 1) * 32) * 4 < 65536 &&
+                  (NS - 1) * STAGE_BYTES + 2 * (NSTEP - 1) * TM * 4 < 65536, "LDS immediate offsets");
+    const uint32_t a_addr = lds_base + (uint32_t)(half * TO + wo * (RA * 32) + l32) * 4u;
+    const uint32_t b_addr = lds_base + (uint32_t)(KS * TO + half * TM + wm * (RB * 32) + l32 * RB) * 4u;
     float av[2][RA];
     BVec  bv[2];
-    auto request = [&](auto jc, auto bufc, uint32_t a_addr, uint32_t b_addr) {
-        constexpr int j = decltype(jc)::value, buf = decltype(bufc)::value;
+    auto request = [&](auto stc, auto jc, auto bufc) {
+        constexpr int st = decltype(stc)::value, j = decltype(jc)::value, buf = decltype(bufc)::value;
         static_for<RA>([&](auto ac) {
             constexpr int a = decltype(ac)::value;
-            lds_read<(2 * j * TO + a * 32) * 4>(av[buf][a], a_addr);
+            lds_read<st * STAGE_BYTES + (2 * j * TO + a * 32) * 4>(av[buf][a], a_addr);
         });
-        lds_read<2 * j * TM * 4>(bv[buf], b_addr);
+        lds_read<st * STAGE_BYTES + 2 * j * TM * 4>(bv[buf], b_addr);
     };
     auto await = [&](auto pendc, auto bufc) {
         constexpr int pend = decltype(pendc)::value, buf = decltype(bufc)::value;
@@ -294,118 +339,121 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
         else lds_wait<pend>(av[buf][0], av[buf][1], av[buf][2], av[buf][3], bv[buf]);
     };
     typedef std::integral_constant<int, 0> I0;
-    typedef std::integral_constant<int, 1> I1;
 
-    // ---- main loop over K, in table-sized chunks (one chunk unless K is huge)
-    for (int kc = 0; kc < p.K; kc += p.tab_cap) {
-        __syncthreads();              // previous tile / chunk has let go of the ring and the table
-        // offset table, Section 3.2: k = (c*Sk + ky)*Sk + kx  ->  ((c*Hi + ky)*Wi + kx)*Nb floats
-        for (int i = t; i < p.tab_cap; i += NT) {
-            const int k = kc + i;
-            u32x2 e = {0u, 0u};
-            if (k < p.K) {
-                const int c  = k / p.SkSk;
-                const int r  = k - c * p.SkSk;
-                const int ky = r / p.Sk;
-                const int kx = r - ky * p.Sk;
-                e.x = (uint32_t)((c * p.Hi + ky) * p.Wi + kx) * (uint32_t)p.Nb * 4u;
-                e.y = ((uint32_t)ky << 16) | (uint32_t)kx;
+    auto main_loop = [&](auto insidec) {
+        // ---- over K, in table-sized chunks (one chunk unless K is huge)
+        for (int kc = 0; kc < p.K; kc += p.tab_cap) {
+            __syncthreads();          // flags / previous chunk have let go of the ring and the table
+            // offset table, Section 3.2: k = (c*Sk + ky)*Sk + kx  ->  ((c*Hi + ky)*Wi + kx)*Nb floats
+            for (int i = t; i < p.tab_cap; i += NT) {
+                const int k = kc + i;
+                u32x2 e = {0u, 0u};
+                if (k < p.K) {
+                    const int c  = k / p.SkSk;
+                    const int r  = k - c * p.SkSk;
+                    const int ky = r / p.Sk;
+                    const int kx = r - ky * p.Sk;
+                    e.x = (uint32_t)((c * p.Hi + ky) * p.Wi + kx) * (uint32_t)p.Nb * 4u;
+                    e.y = ((uint32_t)ky << 16) | (uint32_t)kx;
+                }
+                tab[i] = e;
             }
-            tab[i] = e;
-        }
-        __syncthreads();
+            __syncthreads();
 
-        const int kend = min(p.K, kc + p.tab_cap);
-        const int ns   = (kend - kc + KS - 1) / KS;
-        u32x2 ent[NB];
+            const int kend = min(p.K, kc + p.tab_cap);
+            const int ns   = (kend - kc + KS - 1) / KS;
+            u32x2 ent[NB];
+            ent_addr = tab_base + (uint32_t)brow * 8u;
 
-        // prologue: slabs 0 .. NS-2 in flight, entries of slab NS-1 requested,
-        // slab 0 complete and visible, its first fragments requested
-#pragma unroll
-        for (int s = 0; s < NS - 1; ++s) {
-            if (s < ns) {
-                read_entries(s * KS, ent);
-                wait_entries(ent);
-                issue_A(kc + s * KS, s);
-                issue_B(kc + s * KS, s, ent);
-            }
-        }
-        if (NS - 1 < ns) read_entries((NS - 1) * KS, ent);
-        {
-            const int younger = min(NS - 2, ns - 1);
-            static_for<NS - 1>([&](auto yc) {
-                constexpr int y = decltype(yc)::value;
-                if (younger == y) vmem_wait<y * NL>();
+            // prologue: slabs 0 .. NS-2 in flight, entries of slab NS-1 requested,
+            // slab 0 complete and visible, its first fragments requested
+            static_for<NS - 1>([&](auto sc) {
+                constexpr int s = decltype(sc)::value;
+                if (s < ns) {
+                    read_entries(ent);
+                    wait_entries(ent);
+                    issue_A(sc);
+                    issue_B(sc, insidec, ent);
+                }
             });
-        }
-        bare_barrier();
-        request(I0{}, I0{}, lds_base + a_lane, lds_base + b_lane);
-
-        int stage = 0;                // s % NS
-        for (int s = 0; s < ns; ++s) {
-            const int      nstage   = (stage + 1 == NS) ? 0 : stage + 1;
-            const uint32_t a_addr   = lds_base + stage * STAGE_BYTES + a_lane;
-            const uint32_t b_addr   = lds_base + stage * STAGE_BYTES + b_lane;
-            const uint32_t a_next   = lds_base + nstage * STAGE_BYTES + a_lane;
-            const uint32_t b_next   = lds_base + nstage * STAGE_BYTES + b_lane;
-            const bool     has_next = (s + 1 < ns);
-            const bool     refill   = (s + NS - 1 < ns);
-            int rstage = stage + NS - 1;          // (s + NS - 1) % NS
-            if (rstage >= NS) rstage -= NS;
-
-            static_for<NSTEP>([&](auto jc) {
-                constexpr int j = decltype(jc)::value, cur = j & 1;
-                if constexpr (j == JB) {
-                    if (has_next) {
-                        // own share of slab s+1 landed: slabs s+2 .. s+NS-2 may still be in flight
-                        const int younger = min(NS - 3, ns - 2 - s);
-                        static_for<(NS > 2 ? NS - 2 : 1)>([&](auto yc) {
-                            constexpr int y = decltype(yc)::value;
-                            if (younger == y) vmem_wait<y * NL>();
-                        });
-                        bare_barrier();
-                    }
-                }
-                if constexpr (j + 1 < NSTEP) {
-                    request(std::integral_constant<int, j + 1>{}, std::integral_constant<int, cur ^ 1>{}, a_addr, b_addr);
-                    await(std::integral_constant<int, RA + 1>{}, std::integral_constant<int, cur>{});
-                } else {
-                    if (has_next) {
-                        request(I0{}, std::integral_constant<int, cur ^ 1>{}, a_next, b_next);
-                        await(std::integral_constant<int, RA + 1>{}, std::integral_constant<int, cur>{});
-                    } else {
-                        await(I0{}, std::integral_constant<int, cur>{});
-                    }
-                }
-                static_for<NM>([&](auto mc) {
-                    constexpr int mi = decltype(mc)::value, a = mi / RB, b = mi % RB;
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][a], comp(bv[cur], b), acc[a][b], 0, 0, 0);
-                    if constexpr (j == JB) {
-                        // refill, spread behind the MFMAs of this k-step so that its issue slots are free ones
-                        if constexpr (mi == 0) {
-                            __builtin_amdgcn_sched_barrier(0);
-                            if (refill) {
-                                wait_entries(ent);
-                                issue_A(kc + (s + NS - 1) * KS, rstage);
-                            }
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                        if constexpr (mi == (NM > 1 ? 1 : 0)) {
-                            __builtin_amdgcn_sched_barrier(0);
-                            if (refill) issue_B(kc + (s + NS - 1) * KS, rstage, ent);
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                        if constexpr (mi == (NM > 2 ? 2 : NM - 1)) {
-                            __builtin_amdgcn_sched_barrier(0);
-                            if (s + NS < ns) read_entries((s + NS) * KS, ent);
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                    }
+            if (NS - 1 < ns) read_entries(ent);
+            {
+                const int younger = min(NS - 2, ns - 1);
+                static_for<NS - 1>([&](auto yc) {
+                    constexpr int y = decltype(yc)::value;
+                    if (younger == y) vmem_wait<y * NL>();
                 });
-            });
-            stage = nstage;
+            }
+            bare_barrier();
+            request(I0{}, I0{}, I0{});
+
+            for (int s0 = 0; s0 < ns; s0 += NS) {
+                static_for<NS>([&](auto uc) {
+                    constexpr int u      = decltype(uc)::value;      // stage of this slab
+                    constexpr int unext  = (u + 1) % NS;             // stage of slab s+1
+                    constexpr int ufill  = (u + NS - 1) % NS;        // stage slab s-1 leaves, slab s+NS-1 enters
+                    const int s = s0 + u;
+                    if (s >= ns) return;
+                    const bool has_next = (s + 1 < ns);
+                    const bool refill   = (s + NS - 1 < ns);
+                    const bool more_ent = (s + NS < ns);
+
+                    static_for<NSTEP>([&](auto jc) {
+                        constexpr int j = decltype(jc)::value, cur = j & 1;
+                        if constexpr (j == JB) {
+                            if (has_next) {
+                                // own share of slab s+1 landed: slabs s+2 .. s+NS-2 may still be in flight
+                                const int younger = min(NS - 3, ns - 2 - s);
+                                static_for<(NS > 2 ? NS - 2 : 1)>([&](auto yc) {
+                                    constexpr int y = decltype(yc)::value;
+                                    if (younger == y) vmem_wait<y * NL>();
+                                });
+                                bare_barrier();
+                            }
+                        }
+                        if constexpr (j + 1 < NSTEP) {
+                            request(uc, std::integral_constant<int, j + 1>{}, std::integral_constant<int, cur ^ 1>{});
+                            await(std::integral_constant<int, RA + 1>{}, std::integral_constant<int, cur>{});
+                        } else {
+                            if (has_next) {
+                                request(std::integral_constant<int, unext>{}, I0{}, std::integral_constant<int, cur ^ 1>{});
+                                await(std::integral_constant<int, RA + 1>{}, std::integral_constant<int, cur>{});
+                            } else {
+                                await(I0{}, std::integral_constant<int, cur>{});
+                            }
+                        }
+                        static_for<NM>([&](auto mc) {
+                            constexpr int mi = decltype(mc)::value, a = mi / RB, b = mi % RB;
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][a], comp(bv[cur], b), acc[a][b], 0, 0, 0);
+                            if constexpr (j == JB) {
+                                // refill, spread behind the MFMAs of this k-step
+                                if constexpr (mi == 0) {
+                                    __builtin_amdgcn_sched_barrier(0);
+                                    if (refill) {
+                                        wait_entries(ent);
+                                        issue_A(std::integral_constant<int, ufill>{});
+                                    }
+                                    __builtin_amdgcn_sched_barrier(0);
+                                }
+                                if constexpr (mi == (NM > 1 ? 1 : 0)) {
+                                    __builtin_amdgcn_sched_barrier(0);
+                                    if (refill) issue_B(std::integral_constant<int, ufill>{}, insidec, ent);
+                                    __builtin_amdgcn_sched_barrier(0);
+                                }
+                                if constexpr (mi == (NM > 2 ? 2 : NM - 1)) {
+                                    __builtin_amdgcn_sched_barrier(0);
+                                    if (more_ent) read_entries(ent);
+                                    __builtin_amdgcn_sched_barrier(0);
+                                }
+                            }
+                        });
+                    });
+                });
+            }
         }
-    }
+    };
+    if (interior) main_loop(std::true_type{});
+    else          main_loop(std::false_type{});
 
     // ---- epilogue: out = alpha * acc.  Accumulator register v of lane l in
     // block (a,b) is row 8*(v/4) + 4*(l/32) + v%4, column l%32 of the block.
