@@ -151,7 +151,8 @@ struct Cfg {
     static_assert(A_EL % 64 == 0, "whole waves only may be masked off in the filter copy");
     static_assert(RB == 1 || RB == 2 || RB == 4, "RB");
     static_assert(RA >= 1 && RA <= 4, "RA");
-    static_assert(NS >= 2 && (NS - 2) * NL <= 63, "vmcnt range");
+    // NS >= 3: slab s+1 must already be in flight when slab s reaches its barrier
+    static_assert(NS >= 3 && (NS - 2) * NL <= 63, "ring depth / vmcnt range");
 };
 
 // One TO x TM output tile.  `lds` is the workgroup's dynamic LDS: ring, then table.
@@ -387,69 +388,79 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
             bare_barrier();
             request(I0{}, I0{}, I0{});
 
-            for (int s0 = 0; s0 < ns; s0 += NS) {
-                static_for<NS>([&](auto uc) {
-                    constexpr int u      = decltype(uc)::value;      // stage of this slab
-                    constexpr int unext  = (u + 1) % NS;             // stage of slab s+1
-                    constexpr int ufill  = (u + NS - 1) % NS;        // stage slab s-1 leaves, slab s+NS-1 enters
-                    const int s = s0 + u;
-                    if (s >= ns) return;
-                    const bool has_next = (s + 1 < ns);
-                    const bool refill   = (s + NS - 1 < ns);
-                    const bool more_ent = (s + NS < ns);
+            // One slab.  `steady` = slabs s+1 .. s+NS all exist, so the barrier, the
+            // refill and the entry prefetch are unconditional (no scalar tests
+            // inside the MFMA stream); the last slabs of a chunk take the tested form.
+            auto slab = [&](auto uc, auto steadyc, const int s) {
+                constexpr int  u      = decltype(uc)::value;         // stage of this slab
+                constexpr int  unext  = (u + 1) % NS;                // stage of slab s+1
+                constexpr int  ufill  = (u + NS - 1) % NS;           // stage slab s-1 leaves, slab s+NS-1 enters
+                constexpr bool steady = decltype(steadyc)::value;
+                const bool has_next = steady || (s + 1 < ns);
+                const bool refill   = steady || (s + NS - 1 < ns);
+                const bool more_ent = steady || (s + NS < ns);
 
-                    static_for<NSTEP>([&](auto jc) {
-                        constexpr int j = decltype(jc)::value, cur = j & 1;
-                        if constexpr (j == JB) {
-                            if (has_next) {
-                                // own share of slab s+1 landed: slabs s+2 .. s+NS-2 may still be in flight
+                static_for<NSTEP>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value, cur = j & 1;
+                    if constexpr (j == JB) {
+                        if (has_next) {
+                            // own share of slab s+1 landed: slabs s+2 .. s+NS-2 may still be in flight
+                            if constexpr (steady) {
+                                vmem_wait<(NS - 3 > 0 ? NS - 3 : 0) * NL>();
+                            } else {
                                 const int younger = min(NS - 3, ns - 2 - s);
                                 static_for<(NS > 2 ? NS - 2 : 1)>([&](auto yc) {
                                     constexpr int y = decltype(yc)::value;
                                     if (younger == y) vmem_wait<y * NL>();
                                 });
-                                bare_barrier();
                             }
+                            bare_barrier();
                         }
-                        if constexpr (j + 1 < NSTEP) {
-                            request(uc, std::integral_constant<int, j + 1>{}, std::integral_constant<int, cur ^ 1>{});
+                        // entries were requested a slab ago, the current fragments a k-step ago: no stall
+                        if (refill) wait_entries(ent);
+                    }
+                    if constexpr (j + 1 < NSTEP) {
+                        request(uc, std::integral_constant<int, j + 1>{}, std::integral_constant<int, cur ^ 1>{});
+                        await(std::integral_constant<int, RA + 1>{}, std::integral_constant<int, cur>{});
+                    } else {
+                        if (has_next) {
+                            request(std::integral_constant<int, unext>{}, I0{}, std::integral_constant<int, cur ^ 1>{});
                             await(std::integral_constant<int, RA + 1>{}, std::integral_constant<int, cur>{});
                         } else {
-                            if (has_next) {
-                                request(std::integral_constant<int, unext>{}, I0{}, std::integral_constant<int, cur ^ 1>{});
-                                await(std::integral_constant<int, RA + 1>{}, std::integral_constant<int, cur>{});
-                            } else {
-                                await(I0{}, std::integral_constant<int, cur>{});
+                            await(I0{}, std::integral_constant<int, cur>{});
+                        }
+                    }
+                    static_for<NM>([&](auto mc) {
+                        constexpr int mi = decltype(mc)::value, a = mi / RB, b = mi % RB;
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][a], comp(bv[cur], b), acc[a][b], 0, 0, 0);
+                        if constexpr (j == JB) {
+                            // refill, spread behind the MFMAs of this k-step
+                            if constexpr (mi == 0) {
+                                __builtin_amdgcn_sched_barrier(0);
+                                if (refill) issue_A(std::integral_constant<int, ufill>{});
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                            if constexpr (mi == (NM > 1 ? 1 : 0)) {
+                                __builtin_amdgcn_sched_barrier(0);
+                                if (refill) issue_B(std::integral_constant<int, ufill>{}, insidec, ent);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                            if constexpr (mi == (NM > 2 ? 2 : NM - 1)) {
+                                __builtin_amdgcn_sched_barrier(0);
+                                if (more_ent) read_entries(ent);
+                                __builtin_amdgcn_sched_barrier(0);
                             }
                         }
-                        static_for<NM>([&](auto mc) {
-                            constexpr int mi = decltype(mc)::value, a = mi / RB, b = mi % RB;
-                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][a], comp(bv[cur], b), acc[a][b], 0, 0, 0);
-                            if constexpr (j == JB) {
-                                // refill, spread behind the MFMAs of this k-step
-                                if constexpr (mi == 0) {
-                                    __builtin_amdgcn_sched_barrier(0);
-                                    if (refill) {
-                                        wait_entries(ent);
-                                        issue_A(std::integral_constant<int, ufill>{});
-                                    }
-                                    __builtin_amdgcn_sched_barrier(0);
-                                }
-                                if constexpr (mi == (NM > 1 ? 1 : 0)) {
-                                    __builtin_amdgcn_sched_barrier(0);
-                                    if (refill) issue_B(std::integral_constant<int, ufill>{}, insidec, ent);
-                                    __builtin_amdgcn_sched_barrier(0);
-                                }
-                                if constexpr (mi == (NM > 2 ? 2 : NM - 1)) {
-                                    __builtin_amdgcn_sched_barrier(0);
-                                    if (more_ent) read_entries(ent);
-                                    __builtin_amdgcn_sched_barrier(0);
-                                }
-                            }
-                        });
                     });
                 });
-            }
+            };
+            int s0 = 0;
+            for (; s0 + 2 * NS - 1 < ns; s0 += NS)
+                static_for<NS>([&](auto uc) { slab(uc, std::true_type{}, s0 + decltype(uc)::value); });
+            for (; s0 < ns; s0 += NS)
+                static_for<NS>([&](auto uc) {
+                    if (s0 + decltype(uc)::value < ns) slab(uc, std::false_type{}, s0 + decltype(uc)::value);
+                });
         }
     };
     if (interior) main_loop(std::true_type{});
@@ -544,6 +555,8 @@ typedef Cfg<1, 4, 3, 2, 16, 3, 4> C_o96m256;
 typedef Cfg<1, 4, 2, 2, 16, 3, 4> C_o64m256;
 typedef Cfg<1, 4, 1, 1, 16, 3, 4> C_o32m128;
 typedef Cfg<2, 2, 1, 1, 16, 3, 1> C_o64m64s;
+typedef Cfg<2, 2, 2, 2, 16, 4, 4> C_o128m128x4;
+typedef Cfg<2, 2, 2, 2, 8, 4, 4> C_o128m128k8;
 
 const Entry kEntries[] = {
     make_entry<C_o128m128>("o128m128", 2, 0.85f),
@@ -553,6 +566,8 @@ const Entry kEntries[] = {
     make_entry<C_o64m256>("o64m256", 2, 0.78f),
     make_entry<C_o32m128>("o32m128", 4, 0.70f),
     make_entry<C_o64m64s>("o64m64s", 4, 0.30f),
+    make_entry<C_o128m128x4>("o128m128x4", 1, 0.10f),
+    make_entry<C_o128m128k8>("o128m128k8", 1, 0.10f),
 };
 constexpr int kNumEntries = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
 
