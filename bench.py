@@ -30,23 +30,34 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def time_layer(torch, B, layer, d_in, d_f, out, steps, warmup, variant):
-    """Events on the launch stream (torch's current stream) around `steps` launches."""
-    for _ in range(warmup):
-        B.mdnn_conv_fprop(d_in, d_f, layer.stride, layer.pad, layer.alpha, out=out, variant=variant)
+def time_layer(torch, B, layer, d_in, d_f, out, steps, warmup, variant, min_warm_ms=0.0):
+    """Events on the launch stream (torch's current stream) around `steps` launches.
+    `warmup` untimed launches first, and more until `min_warm_ms` of GPU time has
+    passed: the clocks of an idle GPU need tens of milliseconds of load to ramp up."""
+    def launch(n):
+        for _ in range(n):
+            B.mdnn_conv_fprop(d_in, d_f, layer.stride, layer.pad, layer.alpha, out=out, variant=variant)
+    w0, w1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    w0.record()
+    launch(max(warmup, 1))
+    w1.record()
     torch.cuda.synchronize()
+    warm_ms = w0.elapsed_time(w1)
+    if warm_ms < min_warm_ms:
+        per = warm_ms / max(warmup, 1)
+        launch(int((min_warm_ms - warm_ms) / max(per, 1e-3)) + 1)
+        torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record()
-    for _ in range(steps):
-        B.mdnn_conv_fprop(d_in, d_f, layer.stride, layer.pad, layer.alpha, out=out, variant=variant)
+    launch(steps)
     e1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     return e0.elapsed_time(e1) / steps, wall_ms / steps
 
 
-def layer_report(torch, B, W, name, steps, warmup, variant=None):
+def layer_report(torch, B, W, name, steps, warmup, variant=None, min_warm_ms=0.0):
     L = W.LAYERS[name]
     inp, filt = W.make_inputs(L)
     d_in, d_f = torch.from_numpy(inp).cuda(), torch.from_numpy(filt).cuda()
@@ -54,7 +65,7 @@ def layer_report(torch, B, W, name, steps, warmup, variant=None):
     assert st == 0
     out = torch.empty((L.No, Ho, Wo, L.Nb), dtype=torch.float32, device="cuda")
     flops = B.mdnn_conv_flops(L.Nb, Wo, Ho, L.Nc, L.No, L.Sk)
-    ev_ms, wall_ms = time_layer(torch, B, L, d_in, d_f, out, steps, warmup, variant)
+    ev_ms, wall_ms = time_layer(torch, B, L, d_in, d_f, out, steps, warmup, variant, min_warm_ms)
     tflops = flops / (ev_ms * 1e-3) / 1e12
     nbytes = 4 * (inp.size + filt.size + out.numel())
     rep = {
@@ -75,7 +86,7 @@ def cpu_baseline(W, name):
 
     L = W.LAYERS[name]
     inp, filt = W.make_inputs(L)
-    No_s = max(1, min(L.No, {"vgg": 96, "conv2": 192}.get(name, L.No)))
+    No_s = L.No          # whole layer: a few seconds on 16 cores, ~15 s on 8
     fs = np.ascontiguousarray(filt[..., :No_s])
     Wo, Ho = oracle.out_dims(L.Wi, L.Hi, L.Sk, L.stride, L.pad)
     flops = oracle.flops(L.Nb, Wo, Ho, L.Nc, No_s, L.Sk)
@@ -84,14 +95,14 @@ def cpu_baseline(W, name):
     dt = time.perf_counter() - t0
     return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.max_threads(),
             "kind": "oracle", "seconds": round(dt, 2),
-            "sample": f"first {No_s} of {L.No} output filters of layer {name}, all positions, whole batch"}
+            "sample": f"whole layer {name}: all {No_s} output filters, all positions, whole batch, one pass"}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="vgg", choices=["tiny", "conv1", "conv2", "conv3", "vgg"])
     ap.add_argument("--variant", default=None, help="pin a tile variant for the headline workload")
     ap.add_argument("--no-layers", action="store_true", help="skip the per-layer table")
@@ -159,7 +170,7 @@ def main():
                 layers[name] = rep
                 continue
             steps = {"tiny": 200, "conv1": 50, "conv2": 50, "conv3": 100, "vgg": 30}[name]
-            r, _ = layer_report(torch, B, W, name, steps, 5)
+            r, _ = layer_report(torch, B, W, name, steps, 5, min_warm_ms=100.0)
             layers[name] = r
             log(f"[bench] {name}: {r['ms']} ms, {r['tflops']} TFLOP/s ({100 * r['frac_peak']:.1f}%) "
                 f"variant={r['variant']}")

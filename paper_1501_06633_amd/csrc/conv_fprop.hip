@@ -53,6 +53,11 @@ namespace {
 constexpr uint32_t kOutOfRange = 0xFFFFFFFFu;   // beyond any buffer of < 2^32 bytes
 constexpr int      kRsrcWord3  = 0x00020000;    // raw 32-bit-data buffer descriptor, gfx9 family
 
+// How a tile treats taps that fall into the zero apron (chosen per tile, uniform):
+constexpr int kTapNone = 0;   // no patch of the tile touches the apron: no test at all
+constexpr int kTapMask = 1;   // Sk*Sk <= 32: per-thread bit mask of apron taps, table carries the tap index
+constexpr int kTapTest = 2;   // any Sk: table carries (ky,kx), two range compares per copy
+
 // ---- compile-time loop (asm immediates must be constants)
 template <class F, int... I>
 __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>)
@@ -166,7 +171,7 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
     constexpr int ACCESS = 4 * VW;    // bytes per lane per global -> LDS copy
     typedef typename VecOf<RB>::type BVec;
 
-    u32x2* tab = reinterpret_cast<u32x2*>(lds + C::ring_bytes);   // [tab_cap] {byte offset, ky<<16|kx}
+    u32x2* tab = reinterpret_cast<u32x2*>(lds + C::ring_bytes);   // [tab_cap] {byte offset, tap id}
     const uint32_t lds_base = (uint32_t)(uintptr_t)LDS_PTR(lds);
     const uint32_t tab_base = lds_base + C::ring_bytes;
 
@@ -224,6 +229,17 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
         interior = (__builtin_amdgcn_readfirstlane(all) != 0);
     }
 
+    const bool small_filter = (p.SkSk <= 32);
+    uint32_t   apron_taps = 0;        // bit r set: tap r = ky*Sk + kx of this thread's patch is in the apron
+    if (!interior && small_filter) {
+        int ky = 0, kx = 0;
+        for (int r = 0; r < p.SkSk; ++r) {
+            const bool ok = ((uint32_t)(iy0 + ky) < (uint32_t)p.Hi) & ((uint32_t)(ix0 + kx) < (uint32_t)p.Wi);
+            apron_taps |= (ok ? 0u : 1u) << r;
+            if (++kx == p.Sk) { kx = 0; ++ky; }
+        }
+    }
+
     f32x16 acc[RA][RB];
 #pragma unroll
     for (int a = 0; a < RA; ++a)
@@ -267,13 +283,16 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
     // = patch base + table[k]; a tap in the apron gets an out-of-range offset
     // and reads as 0.  Table rows k >= K hold offset 0: they fetch finite data
     // (or 0) that meets a zero filter row.
-    auto issue_B = [&](auto stc, auto insidec, const u32x2 (&ent)[NB]) {
-        constexpr int  st     = decltype(stc)::value;
-        constexpr bool inside = decltype(insidec)::value;
+    auto issue_B = [&](auto stc, auto modec, const u32x2 (&ent)[NB]) {
+        constexpr int st   = decltype(stc)::value;
+        constexpr int mode = decltype(modec)::value;
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             uint32_t off = pbase + ent[i].x;
-            if constexpr (!inside) {
+            if constexpr (mode == kTapMask) {
+                // entry.y = tap index r; bit r of apron_taps set -> all ones -> out of range
+                off |= (uint32_t)__builtin_amdgcn_sbfe((int)apron_taps, ent[i].y, 1u);
+            } else if constexpr (mode == kTapTest) {
                 const int  ky = (int)ent[i].y >> 16;
                 const int  kx = (int)(ent[i].y & 0xFFFFu);
                 const bool ok = ((uint32_t)(iy0 + ky) < (uint32_t)p.Hi) & ((uint32_t)(ix0 + kx) < (uint32_t)p.Wi);
@@ -341,7 +360,7 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
     };
     typedef std::integral_constant<int, 0> I0;
 
-    auto main_loop = [&](auto insidec) {
+    auto main_loop = [&](auto modec) {
         // ---- over K, in table-sized chunks (one chunk unless K is huge)
         for (int kc = 0; kc < p.K; kc += p.tab_cap) {
             __syncthreads();          // flags / previous chunk have let go of the ring and the table
@@ -355,7 +374,7 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
                     const int ky = r / p.Sk;
                     const int kx = r - ky * p.Sk;
                     e.x = (uint32_t)((c * p.Hi + ky) * p.Wi + kx) * (uint32_t)p.Nb * 4u;
-                    e.y = ((uint32_t)ky << 16) | (uint32_t)kx;
+                    e.y = small_filter ? (uint32_t)r : (((uint32_t)ky << 16) | (uint32_t)kx);
                 }
                 tab[i] = e;
             }
@@ -374,7 +393,7 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
                     read_entries(ent);
                     wait_entries(ent);
                     issue_A(sc);
-                    issue_B(sc, insidec, ent);
+                    issue_B(sc, modec, ent);
                 }
             });
             if (NS - 1 < ns) read_entries(ent);
@@ -442,7 +461,7 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
                             }
                             if constexpr (mi == (NM > 1 ? 1 : 0)) {
                                 __builtin_amdgcn_sched_barrier(0);
-                                if (refill) issue_B(std::integral_constant<int, ufill>{}, insidec, ent);
+                                if (refill) issue_B(std::integral_constant<int, ufill>{}, modec, ent);
                                 __builtin_amdgcn_sched_barrier(0);
                             }
                             if constexpr (mi == (NM > 2 ? 2 : NM - 1)) {
@@ -463,8 +482,9 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
                 });
         }
     };
-    if (interior) main_loop(std::true_type{});
-    else          main_loop(std::false_type{});
+    if (interior)          main_loop(std::integral_constant<int, kTapNone>{});
+    else if (small_filter) main_loop(std::integral_constant<int, kTapMask>{});
+    else                   main_loop(std::integral_constant<int, kTapTest>{});
 
     // ---- epilogue: out = alpha * acc.  Accumulator register v of lane l in
     // block (a,b) is row 8*(v/4) + 4*(l/32) + v%4, column l%32 of the block.
@@ -555,19 +575,18 @@ typedef Cfg<1, 4, 3, 2, 16, 3, 4> C_o96m256;
 typedef Cfg<1, 4, 2, 2, 16, 3, 4> C_o64m256;
 typedef Cfg<1, 4, 1, 1, 16, 3, 4> C_o32m128;
 typedef Cfg<2, 2, 1, 1, 16, 3, 1> C_o64m64s;
-typedef Cfg<2, 2, 2, 2, 16, 4, 4> C_o128m128x4;
 typedef Cfg<2, 2, 2, 2, 8, 4, 4> C_o128m128k8;
 
 const Entry kEntries[] = {
-    make_entry<C_o128m128>("o128m128", 2, 0.85f),
-    make_entry<C_o256m128>("o256m128", 1, 0.80f),
-    make_entry<C_o128m256>("o128m256", 1, 0.80f),
-    make_entry<C_o96m256>("o96m256", 2, 0.80f),
-    make_entry<C_o64m256>("o64m256", 2, 0.78f),
-    make_entry<C_o32m128>("o32m128", 4, 0.70f),
+    // name, workgroups that fit one CU, sustained fraction of the matrix rate inside full tiles (measured)
+    make_entry<C_o128m128>("o128m128", 2, 0.900f),
+    make_entry<C_o128m128k8>("o128m128k8", 3, 0.905f),
+    make_entry<C_o256m128>("o256m128", 1, 0.83f),
+    make_entry<C_o128m256>("o128m256", 1, 0.83f),
+    make_entry<C_o96m256>("o96m256", 1, 0.86f),
+    make_entry<C_o64m256>("o64m256", 2, 0.885f),
+    make_entry<C_o32m128>("o32m128", 4, 0.80f),
     make_entry<C_o64m64s>("o64m64s", 4, 0.30f),
-    make_entry<C_o128m128x4>("o128m128x4", 1, 0.10f),
-    make_entry<C_o128m128k8>("o128m128k8", 1, 0.10f),
 };
 constexpr int kNumEntries = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
 
