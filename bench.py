@@ -108,6 +108,9 @@ def main():
     ap.add_argument("--no-layers", action="store_true", help="skip the per-layer table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true", help="skip the register-only MFMA ceiling")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy three times (known HBM traffic, to scale "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU by design (one convolution on one MI355X); "
@@ -143,6 +146,14 @@ def main():
                      "unit": "TFLOP/s", "frac": rep["frac_peak"], "traffic": None},
         "frac_of_fp32_matrix_peak": rep["frac_peak"],
     }
+
+    if args.copy_calibration:
+        src = torch.rand(64 * 1024 * 1024, device="cuda")          # 256 MiB read, 256 MiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log("[bench] copy calibration: 3 x copy of 268435456 bytes")
 
     # ---- register-only MFMA loop: what the matrix cores sustain with no memory traffic
     if not args.no_probe:

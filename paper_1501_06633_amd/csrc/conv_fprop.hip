@@ -35,6 +35,7 @@
 // global -> LDS copy (vmcnt(0)) before each LDS read, which defeats the ring.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
 #include <utility>
 
 #include "mdnn_internal.h"
@@ -148,7 +149,11 @@ struct Cfg {
     static constexpr int MG = TM / VW;                // accesses per patch-slab row
     static constexpr int BROWS = NT / MG;             // patch rows one pass of the workgroup covers
     static constexpr int NB = KS / BROWS;             // patch accesses per thread per slab
-    static constexpr int NL = NA + NB;                // global -> LDS copies per thread per slab
+    // global -> LDS copies every wave issues per slab (waves past the end of a
+    // short filter slab skip their filter copy, so only full passes count); the
+    // vmcnt waits are phrased in these, which is exact for most tiles and merely
+    // a little early for the waves that issue one more
+    static constexpr int NL = A_EL / NT + NB;
     static constexpr int STAGE_FLOATS = KS * (TO + TM);
     static constexpr uint32_t ring_bytes = (uint32_t)NS * STAGE_FLOATS * sizeof(float);
     static_assert(VW == 1 || VW == 4, "VW");
@@ -161,7 +166,7 @@ struct Cfg {
 };
 
 // One TO x TM output tile.  `lds` is the workgroup's dynamic LDS: ring, then table.
-template <class C>
+template <class C, int CONTEXT = 0>
 __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* lds, const int o0, const int m0)
 {
     constexpr int WO = C::WO, RA = C::RA, RB = C::RB, KS = C::KS, NS = C::NS, VW = C::VW;
@@ -515,20 +520,61 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
     }
 }
 
-template <class C>
+// A tile cut into SPLIT pieces along the filter dimension: same columns, same
+// threads, same ring depth and slab, TO / SPLIT filters.
+template <class C, int SPLIT> struct PieceOf;
+template <class C> struct PieceOf<C, 2> {
+    static_assert(C::RA % 2 == 0 || (C::WO == 2 && C::RB % 2 == 0), "no way to halve this tile");
+    // halve the per-wave filter blocks when possible, else the filter waves (moved to the column side)
+    typedef typename std::conditional<C::RA % 2 == 0,
+        Cfg<C::WO, C::WM, C::RA / 2, C::RB, C::KS, C::NS, C::VW>,
+        Cfg<1, C::WM * 2, C::RA, C::RB / 2, C::KS, C::NS, C::VW>>::type type;
+};
+template <class C> struct PieceOf<C, 4> {
+    typedef typename PieceOf<typename PieceOf<C, 2>::type, 2>::type type;
+};
+
+// SPLITS: 1 = whole tiles only; 4 = the kernel also carries the half- and quarter-tile bodies.
+template <class C, int SPLITS>
 __global__ void __launch_bounds__(C::NT) conv_fprop_kernel(const ConvParams p)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     // ---- tile map.  Workgroups are dealt round-robin to the 8 XCDs, each with
     // its own L2: give every XCD a contiguous run of tiles so that neighbouring
     // output coordinates (overlapping patches) and the filter tiles of one
-    // coordinate (same patch) meet in the same L2.
-    const int bid  = blockIdx.x;
-    const int tile = (bid & 7) * p.tiles_per_xcd + (bid >> 3);
-    if (tile >= p.n_tiles) return;                           // uniform per workgroup
-    const int mt = tile / p.n_otiles;
-    const int ot = tile - mt * p.n_otiles;
-    conv_tile<C>(p, lds_raw, ot * C::TO, mt * C::TM);
+    // coordinate (same patch) meet in the same L2.  Whole tiles come first in
+    // launch order; the pieces of the last, partial round of tiles follow, so
+    // that the tail of the launch is made of short workgroups on every CU
+    // instead of long ones on a few (Section 3.4's smaller blocks, used only
+    // where they pay).
+    const int bid   = blockIdx.x;
+    const int whole = 8 * p.tiles_per_xcd;
+    if (bid < whole) {
+        const int tile = (bid & 7) * p.tiles_per_xcd + (bid >> 3);
+        if (tile >= p.n_whole) return;                       // uniform per workgroup
+        const int mt = tile / p.n_otiles;
+        const int ot = tile - mt * p.n_otiles;
+        conv_tile<C>(p, lds_raw, ot * C::TO, mt * C::TM);
+        return;
+    }
+    if constexpr (SPLITS > 1) {
+        const int b     = bid - whole;
+        const int piece = (b & 7) * p.pieces_per_xcd + (b >> 3);
+        if (piece >= p.n_pieces) return;
+        const int tile = p.n_whole + piece / p.split;
+        const int part = piece - (piece / p.split) * p.split;
+        const int mt = tile / p.n_otiles;
+        const int ot = tile - mt * p.n_otiles;
+        if (p.split == 2) {
+            typedef typename PieceOf<C, 2>::type P2;
+            static_assert(P2::NT == C::NT && P2::TM == C::TM && 2 * P2::TO == C::TO, "half tile");
+            conv_tile<P2, 1>(p, lds_raw, ot * C::TO + part * P2::TO, mt * C::TM);
+        } else {
+            typedef typename PieceOf<C, 4>::type P4;
+            static_assert(P4::NT == C::NT && P4::TM == C::TM && 4 * P4::TO == C::TO, "quarter tile");
+            conv_tile<P4, 1>(p, lds_raw, ot * C::TO + part * P4::TO, mt * C::TM);
+        }
+    }
 }
 
 // ---- register-only FP32 MFMA loop: the sustained matrix rate with no memory traffic
@@ -560,11 +606,11 @@ struct Entry {
     uint32_t    ring_bytes;
 };
 
-template <class C>
+template <class C, int SPLITS = 1>
 constexpr Entry make_entry(const char* name, int wg_per_cu, float eff)
 {
-    return Entry{VariantInfo{name, C::TO, C::TM, C::KS, C::NT, C::VW == 4 ? 1 : 0, wg_per_cu, eff},
-                 &conv_fprop_kernel<C>, C::ring_bytes};
+    return Entry{VariantInfo{name, C::TO, C::TM, C::KS, C::NT, C::VW == 4 ? 1 : 0, wg_per_cu, eff, SPLITS},
+                 &conv_fprop_kernel<C, SPLITS>, C::ring_bytes};
 }
 
 //          WO WM RA RB KS NS VW
@@ -579,8 +625,8 @@ typedef Cfg<2, 2, 2, 2, 8, 4, 4> C_o128m128k8;
 
 const Entry kEntries[] = {
     // name, workgroups that fit one CU, sustained fraction of the matrix rate inside full tiles (measured)
-    make_entry<C_o128m128>("o128m128", 2, 0.900f),
-    make_entry<C_o128m128k8>("o128m128k8", 3, 0.905f),
+    make_entry<C_o128m128, 4>("o128m128", 2, 0.900f),
+    make_entry<C_o128m128k8, 4>("o128m128k8", 3, 0.905f),
     make_entry<C_o256m128>("o256m128", 1, 0.83f),
     make_entry<C_o128m256>("o128m256", 1, 0.83f),
     make_entry<C_o96m256>("o96m256", 1, 0.86f),
@@ -609,7 +655,7 @@ int launch_variant(int i, const ConvParams& p, void* stream)
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (err != hipSuccess) return (int)err;
     }
-    const dim3 grid((unsigned)(8 * p.tiles_per_xcd)), block((unsigned)e.info.threads);
+    const dim3 grid((unsigned)(8 * p.tiles_per_xcd + 8 * p.pieces_per_xcd)), block((unsigned)e.info.threads);
     hipLaunchKernelGGL(e.fn, grid, block, lds, static_cast<hipStream_t>(stream), p);
     err = hipGetLastError();
     return (int)err;

@@ -67,6 +67,26 @@ double variant_cost(const mdnn::VariantInfo& v, int No, int64_t M)
     return (double)rounds * v.tile_o * v.tile_m / v.eff;
 }
 
+// Tail balancing.  With T tiles on 256 compute units the last T mod 256 tiles form
+// a partial round that keeps a few units busy for a whole tile time.  Cutting
+// each of them into 2 or 4 pieces (less efficient, but short) can end the launch
+// sooner: the partial round then costs ceil(r*f/256)/f tile times, divided by the
+// pieces' relative efficiency.
+void choose_split(const mdnn::VariantInfo& v, int n_tiles, int* n_whole, int* split)
+{
+    *n_whole = n_tiles;
+    *split = 1;
+    const int r = n_tiles % kComputeUnits;
+    if (r == 0 || v.max_split < 2) return;
+    static const double rel_eff[5] = {0, 1.0, 0.93, 0, 0.85};
+    double best = 1.0;
+    for (int f = 2; f <= v.max_split; f *= 2) {
+        const double rounds = (double)((r * f + kComputeUnits - 1) / kComputeUnits) / f / rel_eff[f];
+        if (rounds < best - 0.05) { best = rounds; *split = f; }
+    }
+    if (*split > 1) *n_whole = n_tiles - r;
+}
+
 int choose(int Nb, int No, int64_t M)
 {
     int    best = -1;
@@ -173,7 +193,10 @@ mdnn_status mdnn_conv_fprop_variant(const float* in, const float* filt, float* o
     const int64_t n_tiles = (int64_t)p.n_otiles * p.n_mtiles;
     if (n_tiles > ((int64_t)1 << 28)) return MDNN_ETOOBIG;
     p.n_tiles = (int)n_tiles;
-    p.tiles_per_xcd = div_up(n_tiles, 8);
+    choose_split(vi, p.n_tiles, &p.n_whole, &p.split);
+    p.n_pieces = (p.n_tiles - p.n_whole) * p.split;
+    p.tiles_per_xcd = div_up(p.n_whole, 8);
+    p.pieces_per_xcd = div_up(p.n_pieces, 8);
     const int kpad = div_up(g.K, vi.kslab) * vi.kslab;
     p.tab_cap = kpad < kMaxTabEntries ? kpad : kMaxTabEntries;
     p.in_bytes = (uint32_t)g.in_bytes;

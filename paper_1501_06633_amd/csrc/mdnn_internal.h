@@ -21,7 +21,13 @@ struct ConvParams {
     int n_otiles;        // tiles along No
     int n_mtiles;        // tiles along M
     int n_tiles;         // n_otiles * n_mtiles
-    int tiles_per_xcd;   // ceil(n_tiles / 8)
+    // Tail balancing: tiles [0, n_whole) run whole; each of the last n_tiles - n_whole tiles is
+    // cut along the filter dimension into split (1, 2 or 4) pieces that run as separate workgroups.
+    int n_whole;
+    int split;
+    int n_pieces;        // (n_tiles - n_whole) * split
+    int tiles_per_xcd;   // ceil(n_whole / 8)
+    int pieces_per_xcd;  // ceil(n_pieces / 8)
     int tab_cap;         // offset-table entries resident in LDS at once (multiple of the K slab)
     uint32_t in_bytes;   // byte size of in   (buffer-resource range: loads beyond it return 0)
     uint32_t filt_bytes; // byte size of filt
@@ -38,6 +44,7 @@ struct VariantInfo {
     int vec;             // 1: 16-byte loads/stores, needs Nb % 4 == 0 and No % 4 == 0
     int est_wg_per_cu;   // workgroups expected to be co-resident on one compute unit
     float eff;           // sustained fraction of the matrix rate inside a full tile (measured)
+    int max_split;       // 1, 2 or 4: finest cut of a tile this variant's kernel can run
 };
 
 int                variant_count();
