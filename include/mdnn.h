@@ -15,6 +15,7 @@
 #ifndef MDNN_H_
 #define MDNN_H_
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -27,8 +28,9 @@ typedef enum mdnn_status {
                            non-finite alpha, unknown variant name */
     MDNN_ENULL   = 2,   /* a required pointer is NULL */
     MDNN_EALIGN  = 3,   /* a tensor pointer is not 16-byte aligned */
-    MDNN_ETOOBIG = 4,   /* a tensor is 2^32 bytes or larger (32-bit byte offsets are used on the
-                           device, the same kind of limit Section 3.1 notes for texture indices) */
+    MDNN_ETOOBIG = 4,   /* in or out is 2^32 bytes or larger, or filt 2^31 bytes or larger (32-bit byte
+                           offsets are used on the device, the same kind of limit Section 3.1 notes
+                           for texture indices) */
     MDNN_ELAUNCH = 5    /* the HIP runtime refused the launch (hipGetLastError() != hipSuccess) */
 } mdnn_status;
 
@@ -91,6 +93,17 @@ const char* mdnn_variant_name(int i);
  * anything (host only).  Returns NULL if the geometry is invalid. */
 const char* mdnn_choose_variant(int Nb, int Wi, int Hi, int Nc, int No,
                                 int Sk, int stride, int pad);
+
+/*
+ * Describe, as one line of text, how a problem would be launched: variant, tile
+ * shape, number of tiles, how the last partial round of tiles is cut into
+ * smaller pieces (the other block sizes Section 3.4 proposes), grid and LDS
+ * size.  Host only, launches nothing.  `variant` as in mdnn_conv_fprop_variant.
+ * `text` receives at most text_size bytes including the terminating 0.
+ */
+mdnn_status mdnn_describe_launch(int Nb, int Wi, int Hi, int Nc, int No,
+                                 int Sk, int stride, int pad, const char* variant,
+                                 char* text, size_t text_size);
 
 /*
  * Measurement aid for the efficiency metric of Section 3.3 (actual over peak

@@ -49,6 +49,8 @@ def lib() -> ctypes.CDLL:
     L.mdnn_variant_name.restype = s
     L.mdnn_choose_variant.argtypes = [i] * 8
     L.mdnn_choose_variant.restype = s
+    L.mdnn_describe_launch.argtypes = [i] * 8 + [s, ctypes.c_char_p, ctypes.c_size_t]
+    L.mdnn_describe_launch.restype = i
     L.mdnn_mfma_peak_probe.argtypes = [p, i, i, i, ctypes.POINTER(ctypes.c_uint64), p]
     L.mdnn_mfma_peak_probe.restype = i
     _lib = L
@@ -78,6 +80,20 @@ def mdnn_variant_names():
 def mdnn_choose_variant(Nb, Wi, Hi, Nc, No, Sk, stride, pad):
     r = lib().mdnn_choose_variant(Nb, Wi, Hi, Nc, No, Sk, stride, pad)
     return r.decode() if r else None
+
+
+def mdnn_describe_launch(Nb, Wi, Hi, Nc, No, Sk, stride, pad, variant=None) -> dict:
+    """Launch plan as a dict (variant, tiles, whole, split, pieces, grid, lds_bytes, ...)."""
+    buf = ctypes.create_string_buffer(512)
+    st = lib().mdnn_describe_launch(Nb, Wi, Hi, Nc, No, Sk, stride, pad,
+                                    variant.encode() if variant else None, buf, len(buf))
+    if st != MDNN_OK:
+        raise MdnnError(st, "mdnn_describe_launch")
+    out = {}
+    for item in buf.value.decode().split():
+        k, v = item.split("=", 1)
+        out[k] = int(v) if v.lstrip("-").isdigit() else v
+    return out
 
 
 def mdnn_conv_fprop_raw(in_ptr, filt_ptr, out_ptr, Nb, Wi, Hi, Nc, No, Sk, stride, pad, alpha,

@@ -2,6 +2,7 @@
 // tile-variant choice.  No HIP call happens in this file; launches go through
 // mdnn::launch_variant().
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 
 #include "mdnn_internal.h"
@@ -39,7 +40,9 @@ mdnn_status check_geometry(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int s
     g->in_bytes   = bytes(Nc, Hi, Wi, Nb);
     g->filt_bytes = bytes(Nc, Sk, Sk, No);
     g->out_bytes  = bytes(No, Ho, Wo, Nb);
-    if (g->in_bytes >= kFourGiB || g->filt_bytes >= kFourGiB || g->out_bytes >= kFourGiB)
+    // The filter offsets advance one slab past the last row before the loop ends and must not
+    // wrap back into the buffer: keep the filter bank under 2 GiB.
+    if (g->in_bytes >= kFourGiB || g->filt_bytes >= kFourGiB / 2 || g->out_bytes >= kFourGiB)
         return MDNN_ETOOBIG;
     g->Wo = (int)Wo;
     g->Ho = (int)Ho;
@@ -55,29 +58,19 @@ bool variant_usable(const mdnn::VariantInfo& v, int Nb, int No)
     return !v.vec || (Nb % 4 == 0 && No % 4 == 0);
 }
 
-// Cost of a variant: tiles are dealt to 256 compute units, a unit works through
-// its tiles one tile-time after another (co-resident workgroups share the
-// matrix pipe, they do not add to it), and a tile costs its full area even
-// when it hangs over the edge of the output matrix (Section 3.3's point about
-// credit for unnecessary work).
-double variant_cost(const mdnn::VariantInfo& v, int No, int64_t M)
-{
-    const int64_t tiles  = (int64_t)div_up(No, v.tile_o) * div_up(M, v.tile_m);
-    const int64_t rounds = (tiles + kComputeUnits - 1) / kComputeUnits;
-    return (double)rounds * v.tile_o * v.tile_m / v.eff;
-}
-
 // Tail balancing.  With T tiles on 256 compute units the last T mod 256 tiles form
 // a partial round that keeps a few units busy for a whole tile time.  Cutting
 // each of them into 2 or 4 pieces (less efficient, but short) can end the launch
 // sooner: the partial round then costs ceil(r*f/256)/f tile times, divided by the
 // pieces' relative efficiency.
-void choose_split(const mdnn::VariantInfo& v, int n_tiles, int* n_whole, int* split)
+// Returns the cost of the partial round in tile times (0 if there is none).
+double choose_split(const mdnn::VariantInfo& v, int n_tiles, int* n_whole, int* split)
 {
     *n_whole = n_tiles;
     *split = 1;
     const int r = n_tiles % kComputeUnits;
-    if (r == 0 || v.max_split < 2) return;
+    if (r == 0) return 0.0;
+    if (v.max_split < 2) return 1.0;
     static const double rel_eff[5] = {0, 1.0, 0.93, 0, 0.85};
     double best = 1.0;
     for (int f = 2; f <= v.max_split; f *= 2) {
@@ -85,6 +78,23 @@ void choose_split(const mdnn::VariantInfo& v, int n_tiles, int* n_whole, int* sp
         if (rounds < best - 0.05) { best = rounds; *split = f; }
     }
     if (*split > 1) *n_whole = n_tiles - r;
+    return best;
+}
+
+// Cost of a variant: tiles are dealt to 256 compute units, a unit works through
+// its tiles one tile-time after another (co-resident workgroups share the
+// matrix pipe, they do not add to it), and a tile costs its full area even
+// when it hangs over the edge of the output matrix (Section 3.3's point about
+// credit for unnecessary work).  The last, partial round costs what
+// choose_split() makes of it.
+double variant_cost(const mdnn::VariantInfo& v, int No, int64_t M)
+{
+    const int64_t tiles = (int64_t)div_up(No, v.tile_o) * div_up(M, v.tile_m);
+    if (tiles > ((int64_t)1 << 26)) return 1e300;
+    int n_whole, split;
+    const double tail = choose_split(v, (int)tiles, &n_whole, &split);
+    const double rounds = (double)(tiles / kComputeUnits) + tail;
+    return rounds * v.tile_o * v.tile_m / v.eff;
 }
 
 int choose(int Nb, int No, int64_t M)
@@ -105,6 +115,48 @@ int find_variant(const char* name)
     for (int i = 0; i < mdnn::variant_count(); ++i)
         if (std::strcmp(name, mdnn::variant_info(i).name) == 0) return i;
     return -1;
+}
+
+// Everything about a launch that does not depend on the pointers or alpha.
+mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int pad,
+                 const char* variant, mdnn::ConvParams* out, int* variant_index)
+{
+    Geometry g;
+    const mdnn_status gs = check_geometry(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &g);
+    if (gs != MDNN_OK) return gs;
+    int v;
+    if (!variant || !variant[0] || std::strcmp(variant, "auto") == 0) {
+        v = choose(Nb, No, g.M);
+    } else {
+        v = find_variant(variant);
+        if (v >= 0 && !variant_usable(mdnn::variant_info(v), Nb, No)) v = -1;
+    }
+    if (v < 0) return MDNN_EINVAL;
+    const mdnn::VariantInfo& vi = mdnn::variant_info(v);
+
+    mdnn::ConvParams p;
+    p.in = nullptr;  p.filt = nullptr;  p.out = nullptr;
+    p.Nb = Nb;  p.Wi = Wi;  p.Hi = Hi;  p.Nc = Nc;  p.No = No;
+    p.Sk = Sk;  p.stride = stride;  p.pad = pad;
+    p.Wo = g.Wo;  p.Ho = g.Ho;
+    p.K = (int)g.K;  p.SkSk = Sk * Sk;  p.M = (int)g.M;
+    p.n_otiles = div_up(No, vi.tile_o);
+    p.n_mtiles = div_up(g.M, vi.tile_m);
+    const int64_t n_tiles = (int64_t)p.n_otiles * p.n_mtiles;
+    if (n_tiles > ((int64_t)1 << 26)) return MDNN_ETOOBIG;
+    p.n_tiles = (int)n_tiles;
+    choose_split(vi, p.n_tiles, &p.n_whole, &p.split);
+    p.n_pieces = (p.n_tiles - p.n_whole) * p.split;
+    p.tiles_per_xcd = div_up(p.n_whole, 8);
+    p.pieces_per_xcd = div_up(p.n_pieces, 8);
+    const int kpad = div_up(g.K, vi.kslab) * vi.kslab;
+    p.tab_cap = kpad < kMaxTabEntries ? kpad : kMaxTabEntries;
+    p.in_bytes = (uint32_t)g.in_bytes;
+    p.filt_bytes = (uint32_t)g.filt_bytes;
+    p.alpha = 0.0f;
+    *out = p;
+    *variant_index = v;
+    return MDNN_OK;
 }
 
 }  // namespace
@@ -166,44 +218,33 @@ mdnn_status mdnn_conv_fprop_variant(const float* in, const float* filt, float* o
                                     void* stream, const char* variant)
 {
     if (!in || !filt || !out) return MDNN_ENULL;
-    Geometry g;
-    const mdnn_status gs = check_geometry(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &g);
-    if (gs != MDNN_OK) return gs;
+    mdnn::ConvParams p;
+    int v = -1;
+    const mdnn_status ps = plan(Nb, Wi, Hi, Nc, No, Sk, stride, pad, variant, &p, &v);
+    if (ps != MDNN_OK) return ps;
     if (!std::isfinite(alpha)) return MDNN_EINVAL;
     if (((uintptr_t)in | (uintptr_t)filt | (uintptr_t)out) & 15u) return MDNN_EALIGN;
-
-    int v;
-    if (!variant || !variant[0] || std::strcmp(variant, "auto") == 0) {
-        v = choose(Nb, No, g.M);
-    } else {
-        v = find_variant(variant);
-        if (v >= 0 && !variant_usable(mdnn::variant_info(v), Nb, No)) v = -1;
-    }
-    if (v < 0) return MDNN_EINVAL;
-    const mdnn::VariantInfo& vi = mdnn::variant_info(v);
-
-    mdnn::ConvParams p;
     p.in = in;  p.filt = filt;  p.out = out;
-    p.Nb = Nb;  p.Wi = Wi;  p.Hi = Hi;  p.Nc = Nc;  p.No = No;
-    p.Sk = Sk;  p.stride = stride;  p.pad = pad;
-    p.Wo = g.Wo;  p.Ho = g.Ho;
-    p.K = (int)g.K;  p.SkSk = Sk * Sk;  p.M = (int)g.M;
-    p.n_otiles = div_up(No, vi.tile_o);
-    p.n_mtiles = div_up(g.M, vi.tile_m);
-    const int64_t n_tiles = (int64_t)p.n_otiles * p.n_mtiles;
-    if (n_tiles > ((int64_t)1 << 28)) return MDNN_ETOOBIG;
-    p.n_tiles = (int)n_tiles;
-    choose_split(vi, p.n_tiles, &p.n_whole, &p.split);
-    p.n_pieces = (p.n_tiles - p.n_whole) * p.split;
-    p.tiles_per_xcd = div_up(p.n_whole, 8);
-    p.pieces_per_xcd = div_up(p.n_pieces, 8);
-    const int kpad = div_up(g.K, vi.kslab) * vi.kslab;
-    p.tab_cap = kpad < kMaxTabEntries ? kpad : kMaxTabEntries;
-    p.in_bytes = (uint32_t)g.in_bytes;
-    p.filt_bytes = (uint32_t)g.filt_bytes;
     p.alpha = alpha;
-
     return mdnn::launch_variant(v, p, stream) == 0 ? MDNN_OK : MDNN_ELAUNCH;
+}
+
+mdnn_status mdnn_describe_launch(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int pad,
+                                 const char* variant, char* text, size_t text_size)
+{
+    if (!text || text_size == 0) return MDNN_ENULL;
+    mdnn::ConvParams p;
+    int v = -1;
+    const mdnn_status ps = plan(Nb, Wi, Hi, Nc, No, Sk, stride, pad, variant, &p, &v);
+    if (ps != MDNN_OK) { text[0] = 0; return ps; }
+    const mdnn::VariantInfo& vi = mdnn::variant_info(v);
+    std::snprintf(text, text_size,
+                  "variant=%s tile=%dx%d kslab=%d threads=%d K=%d M=%d tiles=%d whole=%d split=%d pieces=%d "
+                  "grid=%d lds_bytes=%u table_entries=%d",
+                  vi.name, vi.tile_o, vi.tile_m, vi.kslab, vi.threads, p.K, p.M, p.n_tiles, p.n_whole,
+                  p.split, p.n_pieces, 8 * p.tiles_per_xcd + 8 * p.pieces_per_xcd,
+                  mdnn::variant_lds_bytes(v, p.tab_cap), p.tab_cap);
+    return MDNN_OK;
 }
 
 mdnn_status mdnn_conv_fprop(const float* in, const float* filt, float* out,

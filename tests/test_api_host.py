@@ -33,7 +33,7 @@ def test_exports_every_declared_symbol(L):
     names = declared_functions()
     assert {"mdnn_conv_fprop", "mdnn_conv_fprop_variant", "mdnn_out_dims", "mdnn_conv_flops",
             "mdnn_status_string", "mdnn_variant_count", "mdnn_variant_name",
-            "mdnn_choose_variant", "mdnn_mfma_peak_probe"} <= set(names)
+            "mdnn_choose_variant", "mdnn_describe_launch", "mdnn_mfma_peak_probe"} <= set(names)
     for n in names:
         assert hasattr(L, n), f"libmdnn.so does not export {n}"
 
@@ -91,6 +91,7 @@ def test_too_big(L):
     assert call(Nb=1024, Wi=1024, Hi=1024, Nc=1) == B.MDNN_ETOOBIG          # in = 4 GiB exactly
     assert call(Nb=128, Wi=2048, Hi=2048, Nc=1, No=4) == B.MDNN_ETOOBIG     # out = 8 GiB
     assert call(Nc=65536, Sk=3, No=4096) == B.MDNN_ETOOBIG                  # filt
+    assert call(Nc=16384, Sk=4, No=2048, Hi=8, Wi=8, Nb=4) == B.MDNN_ETOOBIG   # filt = 2 GiB exactly
     assert call(Nb=2**20, Wi=2**20, Hi=2**20, Nc=2**20) == B.MDNN_ETOOBIG   # no wrap-around
 
 
@@ -116,6 +117,24 @@ def test_variant_registry_and_choice(L):
         assert B.mdnn_choose_variant(*shape) in names
     assert B.mdnn_choose_variant(7, 9, 9, 3, 5, 3, 1, 1).endswith("s")     # scalar-load variant
     assert B.mdnn_choose_variant(8, 2, 2, 1, 1, 3, 1, 0) is None          # invalid geometry
+
+
+def test_describe_launch(L):
+    d = B.mdnn_describe_launch(64, 56, 56, 256, 256, 3, 1, 1)
+    assert d["K"] == 2304 and d["M"] == 56 * 56 * 64
+    assert d["variant"] in B.mdnn_variant_names()
+    to, tm = map(int, d["tile"].split("x"))
+    assert d["tiles"] == -(-256 // to) * -(-d["M"] // tm)
+    assert d["whole"] + d["pieces"] // max(d["split"], 1) == d["tiles"]
+    assert d["lds_bytes"] <= 160 * 1024 and d["table_entries"] % d["kslab"] == 0
+    # a pinned variant, a plan with the tail cut in pieces, and the error paths
+    d = B.mdnn_describe_launch(128, 91, 6, 8, 128, 3, 1, 0, "o128m128")
+    assert (d["tiles"], d["whole"], d["split"], d["pieces"]) == (356, 256, 2, 200)
+    with pytest.raises(B.MdnnError):
+        B.mdnn_describe_launch(8, 2, 2, 1, 1, 3, 1, 0)
+    with pytest.raises(B.MdnnError):
+        B.mdnn_describe_launch(8, 9, 9, 1, 4, 3, 1, 0, "nope")
+    assert L.mdnn_describe_launch(8, 9, 9, 1, 4, 3, 1, 0, None, None, 0) == B.MDNN_ENULL
 
 
 def test_status_strings(L):

@@ -152,6 +152,32 @@ def test_mid_size_all_variants_integer_bitwise(env):
         np.testing.assert_array_equal(got, want, err_msg=variant)
 
 
+# ------------------------------------------------- tail pieces (half / quarter tiles)
+TAILS = [
+    # name        Nb  Hi  Wi  Nc  No  Sk st pad alpha  want_split
+    ("halves",    128,  6, 91,  8, 128, 3, 1, 0, 1.0,  2),      # 356 tiles: 100 left over -> halves
+    ("quarters",  128, 10, 39,  8, 128, 3, 1, 0, 0.5,  4),      # 296 tiles:  40 left over -> quarters
+    ("quarters_ragged", 64, 11, 40, 6, 200, 3, 1, 1, 2.0, 4),   # padded, ragged filter tile, 2 pixels per tile
+]
+
+
+@pytest.mark.parametrize("case", TAILS, ids=[c[0] for c in TAILS])
+@pytest.mark.parametrize("variant", ["o128m128", "o128m128k8"])
+def test_tail_pieces_bitwise(env, case, variant):
+    """Launches whose last partial round of tiles is cut into half or quarter
+    tiles: the plan says so, and integer data must match the oracle bit for bit."""
+    _, B, oracle = env
+    name, Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha, want_split = case
+    plan = B.mdnn_describe_launch(Nb, Wi, Hi, Nc, No, Sk, stride, pad, variant)
+    say(f"[parity-tail] case={name} variant={variant} plan={plan}")
+    assert plan["split"] == want_split and plan["pieces"] == (plan["tiles"] - plan["whole"]) * want_split
+    L = W.custom(name, Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha)
+    inp, filt = W.make_int_inputs(L)
+    want = oracle.conv_fprop(inp, filt, stride, pad, alpha, want_abs=False)
+    got = run_gpu(env, L, inp, filt, variant)
+    np.testing.assert_array_equal(got, want)
+
+
 # ------------------------------------------------------------ semantic edge cases
 def test_delta_filter_and_apron_zeros(env):
     _, B, _ = env
