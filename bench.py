@@ -25,6 +25,13 @@ if ROOT not in sys.path:
 PEAK_FP32_MATRIX_TFLOPS = 157.3      # 256 CUs x 256 FLOP/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
 
+# HBM-side bytes per launch (fetched + written), measured with rocprofv3 --pmc FETCH_SIZE and
+# --pmc WRITE_SIZE (one counter per run) on this kernel and scaled by what the same counters read
+# for a plain 256 MiB device copy in the same run (--copy-calibration): factor 2.000 for
+# FETCH_SIZE, 1.000 for WRITE_SIZE.  Not measurable from inside this script; the summary with the
+# commands is profiles/conv_fprop_hbm_traffic_pmc.txt.
+MEASURED_TRAFFIC_BYTES = {"vgg": 1080.8e6, "conv1": 304.8e6, "conv2": 445.5e6, "conv3": 119.9e6}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -141,9 +148,13 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, **L.dims(), "variant": rep["variant"],
+                   "plan": B.mdnn_describe_launch(L.Nb, L.Wi, L.Hi, L.Nc, L.No, L.Sk, L.stride, L.pad, args.variant),
                    "layout": "in CHWN, filt (C,Sk,Sk,No), out (No,Ho,Wo,Nb)"},
         "roofline": {"bound": "mfma", "achieved": rep["tflops"], "peak": PEAK_FP32_MATRIX_TFLOPS,
-                     "unit": "TFLOP/s", "frac": rep["frac_peak"], "traffic": None},
+                     "unit": "TFLOP/s", "frac": rep["frac_peak"],
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if args.variant is None else None,
+                     "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, copy-calibrated)",
+                     "algorithmic_bytes": rep["compulsory_bytes"]},
         "frac_of_fp32_matrix_peak": rep["frac_peak"],
     }
 
