@@ -125,6 +125,14 @@ __device__ __forceinline__ void bare_barrier()
     asm volatile("s_barrier" ::: "memory");
 }
 
+// n / d for an invariant d whose (magic, shift) the host prepared; exact for n < 2^32
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t magic, uint32_t shift)
+{
+    if (magic == 0) return n;                               // d == 1
+    const uint32_t t = __umulhi(n, magic);
+    return (t + ((n - t) >> 1)) >> shift;
+}
+
 template <int N> struct VecOf;
 template <> struct VecOf<1> { typedef float type; };
 template <> struct VecOf<2> { typedef f32x2 type; };
@@ -219,21 +227,11 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
             col_inside = false;
         }
     }
-    // Tiles whose patches never touch the apron (most of them) take a loop
-    // without the per-tap boundary test.  Workgroup-wide AND through LDS.
-    bool interior;
-    {
-        uint32_t* flags = reinterpret_cast<uint32_t*>(lds);
-        __syncthreads();              // previous tile has let go of LDS
-        const bool wave_inside = (__builtin_amdgcn_ballot_w64(col_inside) == __builtin_amdgcn_ballot_w64(true));
-        if (lane == 0) flags[wave] = wave_inside ? 1u : 0u;
-        __syncthreads();
-        uint32_t all = 1u;
-#pragma unroll
-        for (int w = 0; w < NT / 64; ++w) all &= flags[w];
-        interior = (__builtin_amdgcn_readfirstlane(all) != 0);
-    }
-
+    // Waves whose patches never touch the apron (most of them) take a loop
+    // without the per-tap boundary test.  The choice only changes how a lane
+    // forms its own copy offsets; barriers and counts are the same in every
+    // mode, so it can differ from wave to wave.
+    const bool interior = (__builtin_amdgcn_ballot_w64(col_inside) == __builtin_amdgcn_ballot_w64(true));
     const bool small_filter = (p.SkSk <= 32);
     uint32_t   apron_taps = 0;        // bit r set: tap r = ky*Sk + kx of this thread's patch is in the apron
     if (!interior && small_filter) {
@@ -365,33 +363,36 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
     };
     typedef std::integral_constant<int, 0> I0;
 
+    // table row k: {byte offset of (c,ky,kx) in `in`, tap id}; rows k >= K are {0, 0}
+    auto table_entry = [&](int k) -> u32x2 {
+        u32x2 e = {0u, 0u};
+        if (k < p.K) {
+            const uint32_t c  = fast_div((uint32_t)k, p.sksk_magic, p.sksk_shift);
+            const uint32_t r  = (uint32_t)k - c * (uint32_t)p.SkSk;
+            const uint32_t ky = fast_div(r, p.sk_magic, p.sk_shift);
+            const uint32_t kx = r - ky * (uint32_t)p.Sk;
+            e.x = ((c * (uint32_t)p.Hi + ky) * (uint32_t)p.Wi + kx) * (uint32_t)p.Nb * 4u;
+            e.y = small_filter ? r : ((ky << 16) | kx);
+        }
+        return e;
+    };
+
     auto main_loop = [&](auto modec) {
         // ---- over K, in table-sized chunks (one chunk unless K is huge)
         for (int kc = 0; kc < p.K; kc += p.tab_cap) {
-            __syncthreads();          // flags / previous chunk have let go of the ring and the table
-            // offset table, Section 3.2: k = (c*Sk + ky)*Sk + kx  ->  ((c*Hi + ky)*Wi + kx)*Nb floats
-            for (int i = t; i < p.tab_cap; i += NT) {
-                const int k = kc + i;
-                u32x2 e = {0u, 0u};
-                if (k < p.K) {
-                    const int c  = k / p.SkSk;
-                    const int r  = k - c * p.SkSk;
-                    const int ky = r / p.Sk;
-                    const int kx = r - ky * p.Sk;
-                    e.x = (uint32_t)((c * p.Hi + ky) * p.Wi + kx) * (uint32_t)p.Nb * 4u;
-                    e.y = small_filter ? (uint32_t)r : (((uint32_t)ky << 16) | (uint32_t)kx);
-                }
-                tab[i] = e;
-            }
-            __syncthreads();
-
+            if (kc) __syncthreads();  // previous chunk has let go of the ring and the table
             const int kend = min(p.K, kc + p.tab_cap);
             const int ns   = (kend - kc + KS - 1) / KS;
             u32x2 ent[NB];
-            ent_addr = tab_base + (uint32_t)brow * 8u;
+
+            // offset table, Section 3.2: k = (c*Sk + ky)*Sk + kx  ->  ((c*Hi + ky)*Wi + kx)*Nb floats
+            for (int i = t; i < p.tab_cap; i += NT) tab[i] = table_entry(kc + i);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // table rows written ...
+            bare_barrier();                                       // ... and visible
 
             // prologue: slabs 0 .. NS-2 in flight, entries of slab NS-1 requested,
             // slab 0 complete and visible, its first fragments requested
+            ent_addr = tab_base + (uint32_t)brow * 8u;
             static_for<NS - 1>([&](auto sc) {
                 constexpr int s = decltype(sc)::value;
                 if (s < ns) {
@@ -622,6 +623,9 @@ typedef Cfg<1, 4, 2, 2, 16, 3, 4> C_o64m256;
 typedef Cfg<1, 4, 1, 1, 16, 3, 4> C_o32m128;
 typedef Cfg<2, 2, 1, 1, 16, 3, 1> C_o64m64s;
 typedef Cfg<2, 2, 2, 2, 8, 4, 4> C_o128m128k8;
+typedef Cfg<1, 4, 3, 2, 8, 4, 4> C_o96m256k8;
+typedef Cfg<1, 4, 3, 1, 16, 3, 4> C_o96m128;
+typedef Cfg<1, 4, 3, 1, 8, 4, 4> C_o96m128k8;
 
 const Entry kEntries[] = {
     // name, workgroups that fit one CU, sustained fraction of the matrix rate inside full tiles (measured)
@@ -633,6 +637,9 @@ const Entry kEntries[] = {
     make_entry<C_o64m256>("o64m256", 2, 0.885f),
     make_entry<C_o32m128>("o32m128", 4, 0.80f),
     make_entry<C_o64m64s>("o64m64s", 4, 0.30f),
+    make_entry<C_o96m256k8>("o96m256k8", 2, 0.10f),
+    make_entry<C_o96m128>("o96m128", 3, 0.10f),
+    make_entry<C_o96m128k8>("o96m128k8", 3, 0.10f),
 };
 constexpr int kNumEntries = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
 

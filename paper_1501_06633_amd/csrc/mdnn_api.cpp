@@ -53,6 +53,19 @@ mdnn_status check_geometry(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int s
 
 int div_up(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
+// Division by an invariant d >= 1 (Granlund & Montgomery): with l = ceil(log2 d) and
+// magic = floor(2^32 (2^l - d) / d) + 1,  n / d = (t + ((n - t) >> 1)) >> (l - 1),  t = mulhi(n, magic),
+// exact for every 32-bit n.  d = 1 is encoded as magic 0, shift 0 and the same formula with (n - 0) >> 1
+// would halve n, so it gets its own pair: magic = 0xFFFFFFFF.. no: callers treat shift < 0 specially.
+void division_magic(uint32_t d, uint32_t* magic, uint32_t* shift)
+{
+    if (d == 1) { *magic = 0; *shift = 0; return; }        // device code special-cases magic == 0
+    uint32_t l = 0;
+    while (((uint64_t)1 << l) < d) ++l;
+    *magic = (uint32_t)(((((uint64_t)1 << l) - d) << 32) / d + 1);
+    *shift = l - 1;
+}
+
 bool variant_usable(const mdnn::VariantInfo& v, int Nb, int No)
 {
     return !v.vec || (Nb % 4 == 0 && No % 4 == 0);
@@ -140,6 +153,8 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
     p.Sk = Sk;  p.stride = stride;  p.pad = pad;
     p.Wo = g.Wo;  p.Ho = g.Ho;
     p.K = (int)g.K;  p.SkSk = Sk * Sk;  p.M = (int)g.M;
+    division_magic((uint32_t)p.SkSk, &p.sksk_magic, &p.sksk_shift);
+    division_magic((uint32_t)Sk, &p.sk_magic, &p.sk_shift);
     p.n_otiles = div_up(No, vi.tile_o);
     p.n_mtiles = div_up(g.M, vi.tile_m);
     const int64_t n_tiles = (int64_t)p.n_otiles * p.n_mtiles;

@@ -17,6 +17,9 @@ struct ConvParams {
     int Wo, Ho;
     int K;               // Nc*Sk*Sk: rows of the filter matrix / columns of a patch (Section 3)
     int SkSk;            // Sk*Sk
+    // exact division of any n < 2^31 by SkSk and by Sk without a divide instruction:
+    // q = (mulhi(n, magic) + ((n - mulhi(n, magic)) >> 1)) >> shift
+    uint32_t sksk_magic, sksk_shift, sk_magic, sk_shift;
     int M;               // Ho*Wo*Nb: columns of the output seen as a row-major No x M matrix
     int n_otiles;        // tiles along No
     int n_mtiles;        // tiles along M
