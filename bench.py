@@ -65,7 +65,7 @@ def time_layer(torch, B, layer, d_in, d_f, out, steps, warmup, variant, min_warm
 
 
 def layer_report(torch, B, W, name, steps, warmup, variant=None, min_warm_ms=0.0):
-    L = W.LAYERS[name]
+    L = W.LAYERS[name] if name in W.LAYERS else W.TABLE1[name][0]
     inp, filt = W.make_inputs(L)
     d_in, d_f = torch.from_numpy(inp).cuda(), torch.from_numpy(filt).cuda()
     st, Wo, Ho = B.mdnn_out_dims(L.Wi, L.Hi, L.Sk, L.stride, L.pad)
@@ -115,6 +115,9 @@ def main():
     ap.add_argument("--no-layers", action="store_true", help="skip the per-layer table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true", help="skip the register-only MFMA ceiling")
+    ap.add_argument("--table1", action="store_true",
+                    help="also time the ten layer shapes of the paper's Table 1 (minibatch 128, synthetic "
+                         "data) and print MI355X efficiency beside the paper's GTX 980 column")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy three times (known HBM traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -198,6 +201,17 @@ def main():
                 f"variant={r['variant']}")
         result["layers"] = {k: {kk: v[kk] for kk in ("variant", "ms", "tflops", "frac_peak", "compulsory_GBps")}
                             for k, v in layers.items()}
+
+    if args.table1:
+        rows = {}
+        for name in W.TABLE1:
+            L1, paper_ce = W.TABLE1[name]
+            r, _ = layer_report(torch, B, W, name, 40, 5, min_warm_ms=100.0)
+            rows[name] = {"variant": r["variant"], "ms": r["ms"], "tflops": r["tflops"],
+                          "frac_peak": r["frac_peak"], "paper_gtx980_efficiency": paper_ce / 100.0}
+            log(f"[bench] table1 {name:18s} {r['ms']:8.4f} ms {r['tflops']:7.2f} TFLOP/s "
+                f"{100 * r['frac_peak']:5.1f}% of peak   (paper, GTX 980: {paper_ce}%)  variant={r['variant']}")
+        result["table1"] = rows
 
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample ...")

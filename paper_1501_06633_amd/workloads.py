@@ -50,6 +50,29 @@ LAYERS = {
 ORDER = ("tiny", "conv1", "conv2", "conv3", "vgg")
 
 
+# The ten layer shapes of the paper's Table 1 (FPROP, minibatch 128).  Input size,
+# channels, output size, filter count and filter size are the paper's; it prints
+# neither stride nor pad, the values here are the ones that map the printed input
+# size to the printed output size under the floor formula (customary AlexNet-v2 /
+# OverFeat-fast definitions).  `paper_ce` is the paper's maxDNN computational
+# efficiency on a GTX 980 (Table 1, last column): context for a table, never a target.
+TABLE1 = {}
+for _i, (_name, _wi, _nc, _no, _sk, _st, _pad, _ce) in enumerate([
+        ("alexnet_v2.conv1", 224,    3,   64, 11, 4, 2, 93.4),
+        ("alexnet_v2.conv2",  27,   64,  192,  5, 1, 2, 95.5),
+        ("alexnet_v2.conv3",  13,  192,  384,  3, 1, 1, 95.1),
+        ("alexnet_v2.conv4",  13,  384,  256,  3, 1, 1, 95.0),
+        ("alexnet_v2.conv5",  13,  256,  256,  3, 1, 1, 94.6),
+        ("overfeat.L1",      231,    3,   96, 11, 4, 0, 70.3),
+        ("overfeat.L2",       24,   96,  256,  5, 1, 0, 95.6),
+        ("overfeat.L3",       12,  256,  512,  3, 1, 1, 94.4),
+        ("overfeat.L4",       12,  512, 1024,  3, 1, 1, 96.2),
+        ("overfeat.L5",       12, 1024, 1024,  3, 1, 1, 96.3)]):
+    TABLE1[_name] = (Layer(_name, 128, _wi, _wi, _nc, _no, _sk, _st, _pad, 1.0,
+                           "uniform01" if _nc == 3 else "uniform01_relu", "normal_0p01",
+                           SEED_BASE + 50 + _i), _ce)
+
+
 def custom(name, Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha=1.0,
            in_dist="uniform_pm1", filt_dist="uniform_pm1", seed=SEED_BASE + 1000) -> Layer:
     return Layer(name, Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha, in_dist, filt_dist, seed)

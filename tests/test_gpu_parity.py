@@ -103,6 +103,32 @@ def test_layer_integer_data_bitwise(env, name):
     assert np.abs(vals).max() > 0
 
 
+@pytest.mark.parametrize("name", sorted(W.TABLE1))
+def test_paper_table1_shapes_sampled(env, name):
+    """The ten layer shapes of the paper's Table 1 at full size (minibatch 128):
+    30 000 sampled outputs plus the corners against the oracle's one-by-one
+    evaluation, default variant.  Overfeat L4/L5 have K = 4608 / 9216, more than
+    one offset-table chunk."""
+    _, B, oracle = env
+    L, _ = W.TABLE1[name]
+    say(f"[parity-table1] layer={name} seed={L.seed} plan="
+        f"{B.mdnn_describe_launch(L.Nb, L.Wi, L.Hi, L.Nc, L.No, L.Sk, L.stride, L.pad)}")
+    inp, filt = W.make_inputs(L)
+    got = run_gpu(env, L, inp, filt)
+    No, Ho, Wo, Nb = got.shape
+    rng = np.random.default_rng(L.seed)
+    npts = 30000
+    idx = np.stack([rng.integers(0, No, npts), rng.integers(0, Ho, npts),
+                    rng.integers(0, Wo, npts), rng.integers(0, Nb, npts)], axis=1).astype(np.int32)
+    idx[0] = (0, 0, 0, 0)
+    idx[1] = (No - 1, Ho - 1, Wo - 1, Nb - 1)
+    idx[2] = (No - 1, 0, Wo - 1, 0)
+    idx[3] = (0, Ho - 1, 0, Nb - 1)
+    vals, absum = oracle.conv_fprop_points(inp, filt, idx, L.stride, L.pad, L.alpha)
+    o, y, x, n = idx.T
+    check(got[o, y, x, n], vals, absum, L.alpha, name)
+
+
 # ------------------------------------------------------- odd shapes, all variants
 ODD = [
     # name              Nb  Hi  Wi  Nc  No  Sk st pad alpha
