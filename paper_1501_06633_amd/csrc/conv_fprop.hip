@@ -608,9 +608,9 @@ struct Entry {
 };
 
 template <class C, int SPLITS = 1>
-constexpr Entry make_entry(const char* name, int wg_per_cu, float eff)
+constexpr Entry make_entry(const char* name, int wg_per_cu, float eff, float eff_few)
 {
-    return Entry{VariantInfo{name, C::TO, C::TM, C::KS, C::NT, C::VW == 4 ? 1 : 0, wg_per_cu, eff, SPLITS},
+    return Entry{VariantInfo{name, C::TO, C::TM, C::KS, C::NT, C::VW == 4 ? 1 : 0, wg_per_cu, eff, eff_few, SPLITS},
                  &conv_fprop_kernel<C, SPLITS>, C::ring_bytes};
 }
 
@@ -623,23 +623,20 @@ typedef Cfg<1, 4, 2, 2, 16, 3, 4> C_o64m256;
 typedef Cfg<1, 4, 1, 1, 16, 3, 4> C_o32m128;
 typedef Cfg<2, 2, 1, 1, 16, 3, 1> C_o64m64s;
 typedef Cfg<2, 2, 2, 2, 8, 4, 4> C_o128m128k8;
-typedef Cfg<1, 4, 3, 2, 8, 4, 4> C_o96m256k8;
 typedef Cfg<1, 4, 3, 1, 16, 3, 4> C_o96m128;
-typedef Cfg<1, 4, 3, 1, 8, 4, 4> C_o96m128k8;
+
 
 const Entry kEntries[] = {
-    // name, workgroups that fit one CU, sustained fraction of the matrix rate inside full tiles (measured)
-    make_entry<C_o128m128, 4>("o128m128", 2, 0.900f),
-    make_entry<C_o128m128k8, 4>("o128m128k8", 3, 0.905f),
-    make_entry<C_o256m128>("o256m128", 1, 0.83f),
-    make_entry<C_o128m256>("o128m256", 1, 0.83f),
-    make_entry<C_o96m256>("o96m256", 1, 0.86f),
-    make_entry<C_o64m256>("o64m256", 2, 0.885f),
-    make_entry<C_o32m128>("o32m128", 4, 0.80f),
-    make_entry<C_o64m64s>("o64m64s", 4, 0.30f),
-    make_entry<C_o96m256k8>("o96m256k8", 2, 0.10f),
-    make_entry<C_o96m128>("o96m128", 3, 0.10f),
-    make_entry<C_o96m128k8>("o96m128k8", 3, 0.10f),
+    // name, workgroups that fit one CU, measured fraction of the matrix rate: many tiles per CU / few
+    make_entry<C_o128m128, 4>("o128m128", 2, 0.900f, 0.900f),
+    make_entry<C_o128m128k8, 4>("o128m128k8", 3, 0.905f, 0.870f),
+    make_entry<C_o256m128>("o256m128", 1, 0.83f, 0.83f),
+    make_entry<C_o128m256>("o128m256", 1, 0.83f, 0.83f),
+    make_entry<C_o96m256>("o96m256", 2, 0.860f, 0.70f),
+    make_entry<C_o96m128>("o96m128", 3, 0.855f, 0.855f),
+    make_entry<C_o64m256>("o64m256", 2, 0.885f, 0.80f),
+    make_entry<C_o32m128>("o32m128", 4, 0.80f, 0.80f),
+    make_entry<C_o64m64s>("o64m64s", 4, 0.30f, 0.30f),
 };
 constexpr int kNumEntries = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
 

@@ -107,7 +107,8 @@ double variant_cost(const mdnn::VariantInfo& v, int No, int64_t M)
     int n_whole, split;
     const double tail = choose_split(v, (int)tiles, &n_whole, &split);
     const double rounds = (double)(tiles / kComputeUnits) + tail;
-    return rounds * v.tile_o * v.tile_m / v.eff;
+    const double eff = tiles < 4 * kComputeUnits ? v.eff_few : v.eff;
+    return rounds * v.tile_o * v.tile_m / eff;
 }
 
 int choose(int Nb, int No, int64_t M)

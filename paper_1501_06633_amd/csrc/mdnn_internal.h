@@ -46,7 +46,9 @@ struct VariantInfo {
     int threads;         // workgroup size
     int vec;             // 1: 16-byte loads/stores, needs Nb % 4 == 0 and No % 4 == 0
     int est_wg_per_cu;   // workgroups expected to be co-resident on one compute unit
-    float eff;           // sustained fraction of the matrix rate inside a full tile (measured)
+    float eff;           // sustained fraction of the matrix rate with many tiles per compute unit (measured)
+    float eff_few;       // same with fewer than four tiles per compute unit: start-up and drain of
+                         // co-resident workgroups coincide instead of overlapping (measured)
     int max_split;       // 1, 2 or 4: finest cut of a tile this variant's kernel can run
 };
 
