@@ -115,6 +115,9 @@ def main():
     ap.add_argument("--no-layers", action="store_true", help="skip the per-layer table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true", help="skip the register-only MFMA ceiling")
+    ap.add_argument("--block-sizes", action="store_true",
+                    help="time the headline workload with every 16-byte tile variant: the block-size "
+                         "experiment Section 3.4 of the paper asks for")
     ap.add_argument("--table1", action="store_true",
                     help="also time the ten layer shapes of the paper's Table 1 (minibatch 128, synthetic "
                          "data) and print MI355X efficiency beside the paper's GTX 980 column")
@@ -201,6 +204,23 @@ def main():
                 f"variant={r['variant']}")
         result["layers"] = {k: {kk: v[kk] for kk in ("variant", "ms", "tflops", "frac_peak", "compulsory_GBps")}
                             for k, v in layers.items()}
+
+    if args.block_sizes:
+        rows = {}
+        for v in B.mdnn_variant_names():
+            if v.endswith("s"):
+                continue
+            r, _ = layer_report(torch, B, W, args.workload, 30, 5, v, min_warm_ms=100.0)
+            plan = B.mdnn_describe_launch(L.Nb, L.Wi, L.Hi, L.Nc, L.No, L.Sk, L.stride, L.pad, v)
+            to, tm = map(int, plan["tile"].split("x"))
+            rows[v] = {"tile": plan["tile"], "tiles": plan["tiles"], "split": plan["split"],
+                       "ms": r["ms"], "tflops": r["tflops"], "frac_peak": r["frac_peak"],
+                       # operand bytes a workgroup pulls from L2 per FLOP it performs
+                       "l2_bytes_per_flop": round(4.0 * (to + tm) / (2.0 * to * tm), 4),
+                       "l2_to_lds_TBps": round(r["tflops"] * 4.0 * (to + tm) / (2.0 * to * tm), 2)}
+            log(f"[bench] block {v:11s} tile {plan['tile']:8s} {r['ms']:8.4f} ms {r['tflops']:7.2f} TFLOP/s "
+                f"{100 * r['frac_peak']:5.1f}%  L2->LDS {rows[v]['l2_to_lds_TBps']:.2f} TB/s")
+        result["block_sizes"] = rows
 
     if args.table1:
         rows = {}

@@ -621,6 +621,8 @@ typedef Cfg<2, 2, 2, 4, 16, 3, 4> C_o128m256;
 typedef Cfg<1, 4, 3, 2, 16, 3, 4> C_o96m256;
 typedef Cfg<1, 4, 2, 2, 16, 3, 4> C_o64m256;
 typedef Cfg<1, 4, 1, 1, 16, 3, 4> C_o32m128;
+typedef Cfg<1, 2, 1, 1, 16, 3, 4> C_o32m64;
+typedef Cfg<1, 1, 1, 1, 16, 3, 4> C_o32m32;
 typedef Cfg<2, 2, 1, 1, 16, 3, 1> C_o64m64s;
 typedef Cfg<2, 2, 2, 2, 8, 4, 4> C_o128m128k8;
 typedef Cfg<1, 4, 3, 1, 16, 3, 4> C_o96m128;
@@ -636,6 +638,8 @@ const Entry kEntries[] = {
     make_entry<C_o96m128>("o96m128", 3, 0.855f, 0.855f),
     make_entry<C_o64m256>("o64m256", 2, 0.885f, 0.80f),
     make_entry<C_o32m128>("o32m128", 4, 0.80f, 0.80f),
+    make_entry<C_o32m64>("o32m64", 8, 0.55f, 0.55f),
+    make_entry<C_o32m32>("o32m32", 8, 0.35f, 0.35f),
     make_entry<C_o64m64s>("o64m64s", 4, 0.30f, 0.30f),
 };
 constexpr int kNumEntries = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
