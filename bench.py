@@ -118,6 +118,9 @@ def main():
     ap.add_argument("--block-sizes", action="store_true",
                     help="time the headline workload with every 16-byte tile variant: the block-size "
                          "experiment Section 3.4 of the paper asks for")
+    ap.add_argument("--sgemm", action="store_true",
+                    help="time the 1x1 / stride-1 special case, which is a plain SGEMM (the calibration the "
+                         "paper's conclusion leans on), next to the vendor library's fp32 matmul")
     ap.add_argument("--table1", action="store_true",
                     help="also time the ten layer shapes of the paper's Table 1 (minibatch 128, synthetic "
                          "data) and print MI355X efficiency beside the paper's GTX 980 column")
@@ -221,6 +224,41 @@ def main():
             log(f"[bench] block {v:11s} tile {plan['tile']:8s} {r['ms']:8.4f} ms {r['tflops']:7.2f} TFLOP/s "
                 f"{100 * r['frac_peak']:5.1f}%  L2->LDS {rows[v]['l2_to_lds_TBps']:.2f} TB/s")
         result["block_sizes"] = rows
+
+    if args.sgemm:
+        # out (No x M) = filt^T (No x K) . in (K x M) with M = Hi*Wi*Nb: a 1x1 convolution
+        rows = {}
+        for (Mg, Ng, Kg) in [(4096, 4096, 4096), (8192, 8192, 4096), (16384, 4096, 2304)]:
+            Nb, Hi, Wi = 128, 8, Mg // (128 * 8)
+            d_in = torch.rand((Kg, Hi, Wi, Nb), device="cuda") - 0.5
+            d_f = torch.randn((Kg, 1, 1, Ng), device="cuda") * 0.01
+            out = torch.empty((Ng, Hi, Wi, Nb), device="cuda")
+            lay = W.custom("sgemm", Nb, Hi, Wi, Kg, Ng, 1, 1, 0)
+            ms, _ = time_layer(torch, B, lay, d_in, d_f, out, 30, 5, None, min_warm_ms=100.0)
+            fl = 2.0 * Mg * Ng * Kg
+            a2 = d_f.reshape(Kg, Ng).t().contiguous()
+            b2 = d_in.reshape(Kg, Mg)
+            ref = torch.empty((Ng, Mg), device="cuda")
+            for _ in range(10):
+                torch.matmul(a2, b2, out=ref)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(30):
+                torch.matmul(a2, b2, out=ref)
+            e1.record()
+            torch.cuda.synchronize()
+            lib_ms = e0.elapsed_time(e1) / 30
+            same = bool(torch.allclose(out.reshape(Ng, Mg), ref, rtol=1e-3, atol=1e-3))
+            rows[f"{Ng}x{Mg}x{Kg}"] = {"ms": round(ms, 4), "tflops": round(fl / ms / 1e9, 2),
+                                       "frac_peak": round(fl / ms / 1e9 / PEAK_FP32_MATRIX_TFLOPS, 4),
+                                       "vendor_fp32_matmul_ms": round(lib_ms, 4),
+                                       "vendor_fp32_matmul_tflops": round(fl / lib_ms / 1e9, 2),
+                                       "agrees_with_vendor": same,
+                                       "variant": B.mdnn_choose_variant(Nb, Wi, Hi, Kg, Ng, 1, 1, 0)}
+            log(f"[bench] sgemm {Ng}x{Mg}x{Kg}: mdnn 1x1 conv {ms:.4f} ms {fl / ms / 1e9:.1f} TFLOP/s | "
+                f"vendor fp32 matmul {lib_ms:.4f} ms {fl / lib_ms / 1e9:.1f} TFLOP/s | agree={same}")
+        result["sgemm_1x1"] = rows
 
     if args.table1:
         rows = {}
