@@ -204,6 +204,39 @@ def test_tail_pieces_bitwise(env, case, variant):
     np.testing.assert_array_equal(got, want)
 
 
+def test_offsets_beyond_two_gib(env):
+    """An input of 3.0 GiB (byte offsets above 2^31, close to the 4 GiB limit of the
+    32-bit buffer offsets) and a padded geometry whose apron origins wrap around
+    zero: sampled outputs, concentrated on the last channels and on the border,
+    against the oracle's one-by-one evaluation."""
+    torch, B, oracle = env
+    Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha = 128, 64, 64, 1536, 8, 3, 1, 1, 1.0
+    L = W.custom("big_in", Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha, seed=W.SEED_BASE + 77)
+    say(f"[parity-3gib] in bytes = {4 * Nb * Hi * Wi * Nc}")
+    rng = np.random.default_rng(L.seed)
+    inp = rng.integers(-2, 3, size=(Nc, Hi, Wi, Nb), dtype=np.int8).astype(np.float32)
+    filt = np.zeros((Nc, Sk, Sk, No), np.float32)
+    filt[-64:] = rng.integers(-2, 3, size=(64, Sk, Sk, No)).astype(np.float32)    # only the last channels count:
+    filt[:2] = rng.integers(-2, 3, size=(2, Sk, Sk, No)).astype(np.float32)       # offsets > 2^31, and the first two
+    d_in = torch.from_numpy(inp).cuda()
+    d_f = torch.from_numpy(filt).cuda()
+    out = B.mdnn_conv_fprop(d_in, d_f, stride, pad, alpha)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    del d_in
+    npts = 4000
+    idx = np.stack([rng.integers(0, No, npts), rng.integers(0, Hi, npts),
+                    rng.integers(0, Wi, npts), rng.integers(0, Nb, npts)], axis=1).astype(np.int32)
+    idx[:400, 1] = rng.choice([0, Hi - 1], 400)       # top / bottom rows: taps in the apron
+    idx[400:800, 2] = rng.choice([0, Wi - 1], 400)    # left / right columns
+    idx[0] = (0, 0, 0, 0)
+    idx[1] = (No - 1, Hi - 1, Wi - 1, Nb - 1)
+    vals, _ = oracle.conv_fprop_points(inp, filt, idx, stride, pad, alpha)
+    o, y, x, n = idx.T
+    np.testing.assert_array_equal(got[o, y, x, n], vals)          # integer data: exact
+    assert np.abs(vals).max() > 0
+
+
 # ------------------------------------------------------------ semantic edge cases
 def test_delta_filter_and_apron_zeros(env):
     _, B, _ = env
