@@ -521,6 +521,19 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
     }
 }
 
+// Position in visiting order -> column-tile index (see ConvParams::row_tiles).
+__device__ __forceinline__ int column_tile(const ConvParams& p, int seq)
+{
+    if (p.row_tiles == 0) return seq;
+    const int per_strip = p.strip_rows * p.row_tiles;
+    const int strip = seq / per_strip;
+    const int r     = seq - strip * per_strip;
+    const int rows  = min(p.strip_rows, p.Ho - strip * p.strip_rows);   // last strip may be short
+    const int xt    = r / rows;
+    const int y     = strip * p.strip_rows + (r - xt * rows);
+    return y * p.row_tiles + xt;
+}
+
 // A tile cut into SPLIT pieces along the filter dimension: same columns, same
 // threads, same ring depth and slab, TO / SPLIT filters.
 template <class C, int SPLIT> struct PieceOf;
@@ -553,9 +566,9 @@ __global__ void __launch_bounds__(C::NT) conv_fprop_kernel(const ConvParams p)
     if (bid < whole) {
         const int tile = (bid & 7) * p.tiles_per_xcd + (bid >> 3);
         if (tile >= p.n_whole) return;                       // uniform per workgroup
-        const int mt = tile / p.n_otiles;
-        const int ot = tile - mt * p.n_otiles;
-        conv_tile<C>(p, lds_raw, ot * C::TO, mt * C::TM);
+        const int ms = tile / p.n_otiles;
+        const int ot = tile - ms * p.n_otiles;
+        conv_tile<C>(p, lds_raw, ot * C::TO, column_tile(p, ms) * C::TM);
         return;
     }
     if constexpr (SPLITS > 1) {
@@ -564,8 +577,9 @@ __global__ void __launch_bounds__(C::NT) conv_fprop_kernel(const ConvParams p)
         if (piece >= p.n_pieces) return;
         const int tile = p.n_whole + piece / p.split;
         const int part = piece - (piece / p.split) * p.split;
-        const int mt = tile / p.n_otiles;
-        const int ot = tile - mt * p.n_otiles;
+        const int ms = tile / p.n_otiles;
+        const int ot = tile - ms * p.n_otiles;
+        const int mt = column_tile(p, ms);
         if (p.split == 2) {
             typedef typename PieceOf<C, 2>::type P2;
             static_assert(P2::NT == C::NT && P2::TM == C::TM && 2 * P2::TO == C::TO, "half tile");

@@ -11,6 +11,7 @@ namespace {
 
 constexpr int     kComputeUnits = 256;          // MI355X
 constexpr int     kMaxTabEntries = 4096;        // 32 KB of LDS for the offset table
+constexpr int     kStripRows = 8;               // image rows per strip of the 2-D tile order
 constexpr int64_t kFourGiB = (int64_t)1 << 32;
 
 struct Geometry {
@@ -165,6 +166,17 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
     p.n_pieces = (p.n_tiles - p.n_whole) * p.split;
     p.tiles_per_xcd = div_up(p.n_whole, 8);
     p.pieces_per_xcd = div_up(p.n_pieces, 8);
+    // 2-D visiting order of the column tiles (see ConvParams): needs tiles aligned with pixel rows
+    p.row_tiles = 0;
+    p.strip_rows = 1;
+    {
+        const int64_t row_cols = (int64_t)g.Wo * Nb;             // flat columns per row of pixels
+        const bool whole_pixels = (vi.tile_m % Nb == 0) || (Nb % vi.tile_m == 0);
+        if (whole_pixels && row_cols % vi.tile_m == 0 && g.Ho > 1 && Sk > stride) {
+            p.row_tiles = (int)(row_cols / vi.tile_m);
+            p.strip_rows = g.Ho < kStripRows ? g.Ho : kStripRows;
+        }
+    }
     const int kpad = div_up(g.K, vi.kslab) * vi.kslab;
     p.tab_cap = kpad < kMaxTabEntries ? kpad : kMaxTabEntries;
     p.in_bytes = (uint32_t)g.in_bytes;

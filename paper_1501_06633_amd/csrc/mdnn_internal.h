@@ -31,6 +31,13 @@ struct ConvParams {
     int n_pieces;        // (n_tiles - n_whole) * split
     int tiles_per_xcd;   // ceil(n_whole / 8)
     int pieces_per_xcd;  // ceil(n_pieces / 8)
+    // Column-tile order.  When a tile covers whole output pixels and a row of pixels is a whole
+    // number of tiles (row_tiles > 0), column tiles are visited in strips of strip_rows image rows,
+    // column by column inside a strip, so that the tiles in flight on one XCD form a compact 2-D
+    // patch of the image and the overlapping input patches of neighbouring pixels meet in its L2.
+    // row_tiles == 0: plain row-major order.
+    int row_tiles;       // tiles per row of output pixels
+    int strip_rows;
     int tab_cap;         // offset-table entries resident in LDS at once (multiple of the K slab)
     uint32_t in_bytes;   // byte size of in   (buffer-resource range: loads beyond it return 0)
     uint32_t filt_bytes; // byte size of filt
