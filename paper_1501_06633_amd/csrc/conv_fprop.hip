@@ -28,11 +28,17 @@
 // Pipeline (the paper's Section 3.1 double buffering, re-cut for CDNA4):
 // operand slabs of KS patch columns go global -> LDS directly
 // (buffer_load ... lds, no staging registers) into a ring of NS stages, NS-1
-// slabs ahead of the MFMAs; one workgroup barrier per slab; inside a slab the
-// LDS -> VGPR fragment reads run one MFMA k-step ahead of their use.  LDS
-// reads inside the loop are issued through inline asm with hand-counted
-// s_waitcnt: the compiler would otherwise drain every outstanding
-// global -> LDS copy (vmcnt(0)) before each LDS read, which defeats the ring.
+// slabs ahead of the MFMAs; one workgroup barrier per slab; the LDS -> VGPR
+// fragment reads run one MFMA k-step ahead of their use.  LDS reads inside the
+// loop are issued through inline asm with hand-counted s_waitcnt: the compiler
+// would otherwise drain every outstanding global -> LDS copy (vmcnt(0)) before
+// each LDS read, which defeats the ring.
+//
+// What shapes the loop: on this chip a wave's MFMAs do not overlap that wave's
+// other VALU/SALU instructions -- each one costs 4-5 matrix cycles (LDS reads
+// are free) -- so the slab loop carries about twenty bookkeeping instructions
+// per 32 MFMAs: incremental filter offsets, one add per patch copy, LDS
+// addresses as immediates, no scalar tests in the steady state.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -54,8 +60,8 @@ namespace {
 constexpr uint32_t kOutOfRange = 0xFFFFFFFFu;   // beyond any buffer of < 2^32 bytes
 constexpr int      kRsrcWord3  = 0x00020000;    // raw 32-bit-data buffer descriptor, gfx9 family
 
-// How a tile treats taps that fall into the zero apron (chosen per tile, uniform):
-constexpr int kTapNone = 0;   // no patch of the tile touches the apron: no test at all
+// How a wave treats taps that fall into the zero apron (chosen per tile and per wave):
+constexpr int kTapNone = 0;   // none of the wave's patches touches the apron: no test at all
 constexpr int kTapMask = 1;   // Sk*Sk <= 32: per-thread bit mask of apron taps, table carries the tap index
 constexpr int kTapTest = 2;   // any Sk: table carries (ky,kx), two range compares per copy
 
@@ -174,6 +180,9 @@ struct Cfg {
 };
 
 // One TO x TM output tile.  `lds` is the workgroup's dynamic LDS: ring, then table.
+// CONTEXT only tells apart instantiations of one shape reached from different
+// kernels (a quarter of the 128x128 tile is the 32x128 tile): hipcc's host pass
+// rejects the second use of an identical specialisation of this function.
 template <class C, int CONTEXT = 0>
 __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* lds, const int o0, const int m0)
 {

@@ -54,10 +54,11 @@ mdnn_status check_geometry(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int s
 
 int div_up(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
-// Division by an invariant d >= 1 (Granlund & Montgomery): with l = ceil(log2 d) and
-// magic = floor(2^32 (2^l - d) / d) + 1,  n / d = (t + ((n - t) >> 1)) >> (l - 1),  t = mulhi(n, magic),
-// exact for every 32-bit n.  d = 1 is encoded as magic 0, shift 0 and the same formula with (n - 0) >> 1
-// would halve n, so it gets its own pair: magic = 0xFFFFFFFF.. no: callers treat shift < 0 specially.
+// Division by an invariant d (Granlund & Montgomery, "Division by invariant integers using
+// multiplication"): with l = ceil(log2 d) and magic = floor(2^32 (2^l - d) / d) + 1,
+//     n / d = (t + ((n - t) >> 1)) >> (l - 1),   t = mulhi(n, magic),
+// exact for every 32-bit n and every d >= 2.  d = 1 has no such pair and is encoded as magic 0,
+// which the device code treats as "return n".
 void division_magic(uint32_t d, uint32_t* magic, uint32_t* shift)
 {
     if (d == 1) { *magic = 0; *shift = 0; return; }        // device code special-cases magic == 0

@@ -1,0 +1,67 @@
+"""Static checks on the gfx950 code hipcc generates from our own kernel source
+(compiled to assembly here, no GPU needed): the contraction really runs on the
+FP32 matrix cores -- a tolerance alone cannot tell a reduced-precision matrix
+format from fp32 at K ~ 2300 -- operands really go global -> LDS directly,
+nothing spills, and none of the instruction forms this project must avoid
+(packed-FP32 VALU ops, scalar-cache writes) appears.
+"""
+import os
+import re
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def asm(tmp_path_factory):
+    from paper_1501_06633_amd import build
+    out = tmp_path_factory.mktemp("isa") / "conv_fprop.s"
+    flags = [f for f in build.HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
+    cmd = [build.hipcc(), *flags, "-I", os.path.join(ROOT, "include"), "-I", build.CSRC,
+           "-S", "--cuda-device-only", "-o", str(out), build.SOURCES[0]]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert res.returncode == 0, res.stdout[-2000:]
+    return out.read_text()
+
+
+def mnemonics(text):
+    ops = set()
+    for line in text.splitlines():
+        line = line.split(";")[0].strip()
+        if not line or line.startswith(".") or line.endswith(":"):
+            continue
+        ops.add(line.split()[0])
+    return ops
+
+
+def test_contraction_is_fp32_mfma_only(asm):
+    ops = mnemonics(asm)
+    mfma = {o for o in ops if o.startswith(("v_mfma", "v_smfmac"))}
+    assert mfma == {"v_mfma_f32_32x32x2_f32"}, mfma      # no bf16 / f16 / xf32 / i8 / f8 / sparse forms
+    assert asm.count("v_mfma_f32_32x32x2_f32") > 1000    # every variant carries the unrolled loop
+
+
+def test_operands_go_global_to_lds_directly(asm):
+    assert re.search(r"buffer_load_dwordx4 .* lds", asm)
+    assert re.search(r"buffer_load_dword .* lds", asm)   # the scalar-copy variant
+    assert "ds_read_b128" in asm or "ds_read_b64" in asm
+
+
+def test_no_forbidden_instruction_forms(asm):
+    ops = mnemonics(asm)
+    assert not {o for o in ops if o.startswith(("v_pk_add_f32", "v_pk_mul_f32", "v_pk_fma_f32"))}
+    assert not {o for o in ops if o.startswith(("s_store", "s_buffer_store", "s_atomic", "s_buffer_atomic",
+                                                "s_dcache_wb", "s_dcache_inv", "s_scratch_store"))}
+
+
+def test_no_spills_and_register_budget(asm):
+    spills = [int(x) for x in re.findall(r"\.vgpr_spill_count:\s+(\d+)", asm)]
+    sspills = [int(x) for x in re.findall(r"\.sgpr_spill_count:\s+(\d+)", asm)]
+    scratch = [int(x) for x in re.findall(r"\.private_segment_fixed_size:\s+(\d+)", asm)]
+    assert spills and not any(spills) and not any(sspills) and not any(scratch)
+    vgprs = dict(zip(re.findall(r"\.name:\s+(\S+)", asm), map(int, re.findall(r"\.vgpr_count:\s+(\d+)", asm))))
+    # the 128x128 kernels must leave room for three waves per SIMD (512 / 3 = 170 registers)
+    main = [v for k, v in vgprs.items() if "Li2ELi2ELi2ELi2E" in k]
+    assert main and max(main) <= 168, vgprs
