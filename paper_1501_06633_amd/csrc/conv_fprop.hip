@@ -220,9 +220,9 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
     {
         const int m = m0 + VW * q;
         if (m < p.M) {
-            const int pix = m / p.Nb;
+            const int pix = (int)fast_div((uint32_t)m, p.nb_magic, p.nb_shift);
             const int n   = m - pix * p.Nb;
-            const int y   = pix / p.Wo;
+            const int y   = (int)fast_div((uint32_t)pix, p.wo_magic, p.wo_shift);
             const int x   = pix - y * p.Wo;
             iy0 = y * p.stride - p.pad;
             ix0 = x * p.stride - p.pad;
@@ -502,13 +502,47 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
     else                   main_loop(std::integral_constant<int, kTapTest>{});
 
     // ---- epilogue: out = alpha * acc.  Accumulator register v of lane l in
-    // block (a,b) is row 8*(v/4) + 4*(l/32) + v%4, column l%32 of the block.
-    const int ocol = m0 + wm * (RB * 32) + l32 * RB;
+    // block (a,b) is row 8*(v/4) + 4*(l/32) + v%4, column l%32 of the block, so a
+    // lane's RB values of one row are adjacent in memory.  Like the loop, the
+    // epilogue is written to cost few instructions: a tile that lies wholly
+    // inside the output (nearly all do) stores through a wave-uniform row
+    // pointer plus one per-lane 32-bit offset, with no per-row address
+    // arithmetic or bounds test in vector instructions.
+    const int o_wave = o0 + wo * (RA * 32);
+    const int m_wave = m0 + wm * (RB * 32);
+    if (o0 + TO <= p.No && m0 + TM <= p.M) {
+        const uint32_t lane_off = ((uint32_t)(4 * half) * (uint32_t)p.M + (uint32_t)(l32 * RB)) * 4u;
+        const size_t   row_bytes = (size_t)p.M * 4u;
+        char* const    wave_base = reinterpret_cast<char*>(p.out) + ((size_t)o_wave * (size_t)p.M + (size_t)m_wave) * 4u;
+        auto store_rows = [&](auto unitc) {
+            constexpr bool unit = decltype(unitc)::value;       // alpha == 1: store the accumulators as they are
+#pragma unroll
+            for (int a = 0; a < RA; ++a) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    char* row = wave_base + (size_t)(a * 32 + 8 * (v >> 2) + (v & 3)) * row_bytes;   // uniform
+                    BVec w;
+#pragma unroll
+                    for (int b = 0; b < RB; ++b) {
+                        const float x = unit ? acc[a][b][v] : p.alpha * acc[a][b][v];
+                        if constexpr (RB == 1) w = x;
+                        else w[b] = x;
+                    }
+                    *reinterpret_cast<BVec*>(row + lane_off) = w;
+                }
+            }
+        };
+        if (p.alpha == 1.0f) store_rows(std::true_type{});
+        else                 store_rows(std::false_type{});
+        return;
+    }
+    // ragged tile: per-row and per-column tests
+    const int ocol = m_wave + l32 * RB;
 #pragma unroll
     for (int a = 0; a < RA; ++a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int o = o0 + wo * (RA * 32) + a * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+            const int o = o_wave + a * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
             if (o >= p.No) continue;
             float* dst = p.out + (size_t)o * (size_t)p.M + ocol;
             if constexpr (VW == 4) {

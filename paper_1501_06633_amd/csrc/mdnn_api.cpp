@@ -158,6 +158,8 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
     p.K = (int)g.K;  p.SkSk = Sk * Sk;  p.M = (int)g.M;
     division_magic((uint32_t)p.SkSk, &p.sksk_magic, &p.sksk_shift);
     division_magic((uint32_t)Sk, &p.sk_magic, &p.sk_shift);
+    division_magic((uint32_t)Nb, &p.nb_magic, &p.nb_shift);
+    division_magic((uint32_t)g.Wo, &p.wo_magic, &p.wo_shift);
     p.n_otiles = div_up(No, vi.tile_o);
     p.n_mtiles = div_up(g.M, vi.tile_m);
     const int64_t n_tiles = (int64_t)p.n_otiles * p.n_mtiles;

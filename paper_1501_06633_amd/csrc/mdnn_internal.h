@@ -20,6 +20,7 @@ struct ConvParams {
     // exact division of any n < 2^31 by SkSk and by Sk without a divide instruction:
     // q = (mulhi(n, magic) + ((n - mulhi(n, magic)) >> 1)) >> shift
     uint32_t sksk_magic, sksk_shift, sk_magic, sk_shift;
+    uint32_t nb_magic, nb_shift, wo_magic, wo_shift;      // the same for Nb and Wo
     int M;               // Ho*Wo*Nb: columns of the output seen as a row-major No x M matrix
     int n_otiles;        // tiles along No
     int n_mtiles;        // tiles along M
