@@ -685,6 +685,7 @@ typedef Cfg<2, 2, 2, 2, 8, 4, 4> C_o128m128k8;
 typedef Cfg<1, 4, 3, 1, 16, 3, 4> C_o96m128;
 
 
+
 const Entry kEntries[] = {
     // name, workgroups that fit one CU, measured fraction of the matrix rate: many tiles per CU / few
     make_entry<C_o128m128, 4>("o128m128", 2, 0.900f, 0.900f),
