@@ -46,6 +46,8 @@ def _load():
     lib.mdnn_oracle_max_threads.restype = i
     lib.mdnn_oracle_conv_fprop.argtypes = [p, p, p, p, i, i, i, i, i, i, i, i, f, i]
     lib.mdnn_oracle_conv_fprop.restype = i
+    lib.mdnn_oracle_conv_bprop_data.argtypes = [p, p, p, p, i, i, i, i, i, i, i, i, f, i]
+    lib.mdnn_oracle_conv_bprop_data.restype = i
     lib.mdnn_oracle_conv_fprop_points.argtypes = [p, p, p, ctypes.c_int64, p, p,
                                                   i, i, i, i, i, i, i, i, f]
     lib.mdnn_oracle_conv_fprop_points.restype = i
@@ -116,3 +118,26 @@ def conv_fprop_points(inp, filt, idx, stride, pad, alpha):
     if rc:
         raise ValueError("oracle rejected the arguments (index out of range?)")
     return vals, ab
+
+
+def conv_bprop_data(dout, filt, in_hw, stride, pad, alpha, want_abs=True, nthreads=0):
+    """dout (No,Ho,Wo,Nb) f32, filt (Nc,Sk,Sk,No) f32, in_hw = (Hi, Wi) of the forward input
+    -> din (Nc,Hi,Wi,Nb) f32 and, when ``want_abs``, the per-element sum of |products|."""
+    No, Ho, Wo, Nb = dout.shape
+    Nc, Sk, Sk2, No2 = filt.shape
+    Hi, Wi = in_hw
+    if No2 != No or Sk2 != Sk:
+        raise ValueError("filter shape does not match dout")
+    _check(dout, dout.shape, "dout")
+    _check(filt, filt.shape, "filt")
+    if out_dims(Wi, Hi, Sk, stride, pad) != (Wo, Ho):
+        raise ValueError("dout spatial size does not match the forward geometry")
+    din = np.empty((Nc, Hi, Wi, Nb), dtype=np.float32)
+    ab = np.empty((Nc, Hi, Wi, Nb), dtype=np.float64) if want_abs else None
+    rc = _load().mdnn_oracle_conv_bprop_data(
+        dout.ctypes.data, filt.ctypes.data, din.ctypes.data,
+        ab.ctypes.data if ab is not None else None,
+        Nb, Wi, Hi, Nc, No, Sk, stride, pad, float(alpha), int(nthreads))
+    if rc:
+        raise ValueError("oracle rejected the arguments")
+    return (din, ab) if want_abs else din

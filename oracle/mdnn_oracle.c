@@ -31,6 +31,12 @@
  *   - one symmetric pad on all four sides, zeros outside the image;
  *   - alpha is applied once to the finished sum; out is overwritten.
  *
+ * The data gradient (BPROP with respect to the input), which the paper only
+ * conjectures to work the same way (abstract, Section 3.5), is written out too:
+ * it is the adjoint of the map in -> out above, scaled by alpha.  Its pins are
+ * the adjoint identity against the forward function, a scatter-add brute force,
+ * torch's transposed convolution in float64 and delta tests.
+ *
  * Pins (tests/test_oracle_*.py, CPU only): brute-force im2col x GEMM in numpy
  * float64, the 1x1/stride-1 = plain matrix product identity, delta filters,
  * linearity in alpha / additivity, the all-ones closed form, exact-integer
@@ -194,4 +200,79 @@ int mdnn_oracle_conv_fprop_points(const float* in, const float* filt,
         if (abs_val) abs_val[i] = A;
     }
     return bad;
+}
+
+/*
+ * Data gradient of the convolution above (BPROP w.r.t. the input):
+ *   din[c][iy][ix][n] = alpha * sum_{o,ky,kx} dout[o][y][x][n] * filt[c][ky][kx][o]
+ * over those (ky,kx) for which  y = (iy + pad - ky)/stride  and  x = (ix + pad - kx)/stride
+ * are integers inside the output map -- i.e. over every forward term in which
+ * in[c][iy][ix][n] took part.  din has the layout and size of `in`; input
+ * pixels no filter window reaches get 0.  abs_sum as in the forward function.
+ * Loops: c, iy, ix, o, ky, kx, n (n innermost), OpenMP over c only.
+ */
+int mdnn_oracle_conv_bprop_data(const float* dout, const float* filt, float* din,
+                                double* abs_sum,
+                                int Nb, int Wi, int Hi, int Nc, int No,
+                                int Sk, int stride, int pad, float alpha,
+                                int nthreads)
+{
+    int Wo, Ho;
+    if (!dout || !filt || !din) return 1;
+    if (Nb < 1 || Nc < 1 || No < 1) return 1;
+    if (mdnn_oracle_out_dims(Wi, Hi, Sk, stride, pad, &Wo, &Ho)) return 1;
+#ifdef _OPENMP
+    if (nthreads <= 0) nthreads = omp_get_max_threads();
+#else
+    nthreads = 1;
+#endif
+    int failed = 0;
+
+#pragma omp parallel num_threads(nthreads)
+    {
+        double* S = (double*)malloc(sizeof(double) * (size_t)Nb);
+        double* A = (double*)malloc(sizeof(double) * (size_t)Nb);
+        if (!S || !A) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for schedule(dynamic, 1)
+            for (int c = 0; c < Nc; ++c) {
+                for (int iy = 0; iy < Hi; ++iy) {
+                    for (int ix = 0; ix < Wi; ++ix) {
+                        for (int n = 0; n < Nb; ++n) { S[n] = 0.0; A[n] = 0.0; }
+                        for (int o = 0; o < No; ++o) {
+                            for (int ky = 0; ky < Sk; ++ky) {
+                                int ty = iy + pad - ky;                 /* = y * stride */
+                                if (ty < 0 || ty % stride != 0 || ty / stride >= Ho) continue;
+                                for (int kx = 0; kx < Sk; ++kx) {
+                                    int tx = ix + pad - kx;
+                                    if (tx < 0 || tx % stride != 0 || tx / stride >= Wo) continue;
+                                    const float* row = dout +
+                                        (((size_t)o * Ho + ty / stride) * Wo + tx / stride) * (size_t)Nb;
+                                    double w = (double)
+                                        filt[(((size_t)c * Sk + ky) * Sk + kx) * (size_t)No + o];
+                                    for (int n = 0; n < Nb; ++n) {
+                                        double p = (double)row[n] * w;
+                                        S[n] += p;
+                                        A[n] += fabs(p);
+                                    }
+                                }
+                            }
+                        }
+                        size_t base = (((size_t)c * Hi + iy) * Wi + ix) * (size_t)Nb;
+                        for (int n = 0; n < Nb; ++n)
+                            din[base + n] = (float)((double)alpha * S[n]);
+                        if (abs_sum)
+                            for (int n = 0; n < Nb; ++n) abs_sum[base + n] = A[n];
+                    }
+                }
+            }
+        }
+        free(S);
+        free(A);
+    }
+    return failed;
 }
