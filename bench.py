@@ -124,6 +124,10 @@ def main():
     ap.add_argument("--rotating", action="store_true",
                     help="also time the headline workload cycling through enough (in, filt, out) buffer sets "
                          "to exceed L2 + Infinity Cache (>= 1.2 GB), so no launch finds its operands cached")
+    ap.add_argument("--bprop-data", action="store_true",
+                    help="also time the data gradient (BPROP w.r.t. the input, computed by the FPROP kernels on "
+                         "the turned-over filter bank) of the five layers; each call includes the filter "
+                         "rearrangement and, for stride > 1, the dilation of the output gradient")
     ap.add_argument("--sgemm", action="store_true",
                     help="time the 1x1 / stride-1 special case, which is a plain SGEMM (the calibration the "
                          "paper's conclusion leans on), next to the vendor library's fp32 matmul")
@@ -257,6 +261,40 @@ def main():
                               "frac_peak": round(rep["flops"] / rms / 1e9 / PEAK_FP32_MATRIX_TFLOPS, 4)}
         log(f"[bench] rotating {nsets} buffer sets: {rms:.5f} ms/step, {result['rotating']['tflops']} TFLOP/s")
         del sets
+
+    if args.bprop_data:
+        rows = {}
+        for name in W.ORDER:
+            Lb = W.LAYERS[name]
+            st, Wo, Ho = B.mdnn_out_dims(Lb.Wi, Lb.Hi, Lb.Sk, Lb.stride, Lb.pad)
+            _, filt = W.make_inputs(Lb)
+            d_f = torch.from_numpy(filt).cuda()
+            d_g = torch.randn((Lb.No, Ho, Wo, Lb.Nb), device="cuda")
+            din = torch.empty((Lb.Nc, Lb.Hi, Lb.Wi, Lb.Nb), device="cuda")
+            st, need = B.mdnn_conv_bprop_data_workspace(Lb.Nb, Lb.Wi, Lb.Hi, Lb.Nc, Lb.No, Lb.Sk, Lb.stride, Lb.pad)
+            ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+
+            def launch(n):
+                for _ in range(n):
+                    B.mdnn_conv_bprop_data(d_g, d_f, (Lb.Hi, Lb.Wi), Lb.stride, Lb.pad, Lb.alpha, din=din, workspace=ws)
+            launch(5)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); launch(20); e1.record(); torch.cuda.synchronize()
+            per = e0.elapsed_time(e1) / 20
+            launch(int(WARM_MS_FLOOR / max(per, 1e-3)) + 1)
+            torch.cuda.synchronize()
+            steps = {"tiny": 200, "conv1": 20, "conv2": 50, "conv3": 100, "vgg": 30}[name]
+            e0.record(); launch(steps); e1.record(); torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / steps
+            # required work: every forward multiply-add has one counterpart in the gradient
+            fl = B.mdnn_conv_flops(Lb.Nb, Wo, Ho, Lb.Nc, Lb.No, Lb.Sk)
+            rows[name] = {"ms": round(ms, 5), "tflops": round(fl / ms / 1e9, 3),
+                          "frac_peak": round(fl / ms / 1e9 / PEAK_FP32_MATRIX_TFLOPS, 4),
+                          "stride": Lb.stride, "workspace_bytes": need}
+            log(f"[bench] bprop-data {name:6s} {ms:9.5f} ms {rows[name]['tflops']:8.3f} TFLOP/s "
+                f"({100 * rows[name]['frac_peak']:.1f}% of peak, required FLOPs) stride={Lb.stride}")
+        result["bprop_data"] = rows
 
     if args.sgemm:
         # out (No x M) = filt^T (No x K) . in (K x M) with M = Hi*Wi*Nb: a 1x1 convolution

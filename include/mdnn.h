@@ -95,6 +95,37 @@ const char* mdnn_choose_variant(int Nb, int Wi, int Hi, int Nc, int No,
                                 int Sk, int stride, int pad);
 
 /*
+ * Data gradient (BPROP with respect to the input).  The paper builds FPROP only
+ * and states the belief that the same techniques carry over (abstract, Section
+ * 3.5); here they do, literally: the gradient is computed by the FPROP kernels
+ * as a stride-1 convolution of the (zero-dilated) output gradient with the
+ * turned-over, channel/filter-swapped filter bank.
+ *
+ *   dout  device, fp32, [No][Ho][Wo][Nb]   gradient w.r.t. the forward output
+ *   filt  device, fp32, [Nc][Sk][Sk][No]   the forward filter bank, unchanged
+ *   din   device, fp32, [Nc][Hi][Wi][Nb]   fully overwritten
+ *
+ *   din[c][iy][ix][n] = alpha * sum over every forward term in[c][iy][ix][n] took part in of
+ *                       dout[o][y][x][n] * filt[c][ky][kx][o]
+ *   (iy = y*stride - pad + ky, ix likewise); input pixels no window reaches get 0.
+ *
+ * The dimension arguments are those of the FORWARD call.  pad <= Sk - 1 is
+ * required.  `workspace` is device memory of at least the size
+ * mdnn_conv_bprop_data_workspace() reports (16-byte aligned); it receives the
+ * rearranged filter bank and, for stride > 1, the dilated gradient, and may be
+ * reused or freed once the stream has passed this call.  For stride > 1 the
+ * result is correct but the matrix cores also multiply the inserted zeros
+ * (stride^2 times the necessary work).  Same stream, ownership and error rules
+ * as mdnn_conv_fprop.
+ */
+mdnn_status mdnn_conv_bprop_data_workspace(int Nb, int Wi, int Hi, int Nc, int No,
+                                           int Sk, int stride, int pad, size_t* bytes);
+mdnn_status mdnn_conv_bprop_data(const float* dout, const float* filt, float* din,
+                                 void* workspace, size_t workspace_bytes,
+                                 int Nb, int Wi, int Hi, int Nc, int No,
+                                 int Sk, int stride, int pad, float alpha, void* stream);
+
+/*
  * Describe, as one line of text, how a problem would be launched: variant, tile
  * shape, number of tiles, how the last partial round of tiles is cut into
  * smaller pieces (the other block sizes Section 3.4 proposes), grid and LDS

@@ -51,6 +51,10 @@ def lib() -> ctypes.CDLL:
     L.mdnn_choose_variant.restype = s
     L.mdnn_describe_launch.argtypes = [i] * 8 + [s, ctypes.c_char_p, ctypes.c_size_t]
     L.mdnn_describe_launch.restype = i
+    L.mdnn_conv_bprop_data_workspace.argtypes = [i] * 8 + [ctypes.POINTER(ctypes.c_size_t)]
+    L.mdnn_conv_bprop_data_workspace.restype = i
+    L.mdnn_conv_bprop_data.argtypes = [p, p, p, p, ctypes.c_size_t, i, i, i, i, i, i, i, i, f, p]
+    L.mdnn_conv_bprop_data.restype = i
     L.mdnn_mfma_peak_probe.argtypes = [p, i, i, i, ctypes.POINTER(ctypes.c_uint64), p]
     L.mdnn_mfma_peak_probe.restype = i
     _lib = L
@@ -138,6 +142,56 @@ def mdnn_conv_fprop(inp, filt, stride, pad, alpha=1.0, out=None, variant=None, s
     if st != MDNN_OK:
         raise MdnnError(st, "mdnn_conv_fprop")
     return out
+
+
+def mdnn_conv_bprop_data_workspace(Nb, Wi, Hi, Nc, No, Sk, stride, pad):
+    """-> (status, bytes)"""
+    n = ctypes.c_size_t(0)
+    st = lib().mdnn_conv_bprop_data_workspace(Nb, Wi, Hi, Nc, No, Sk, stride, pad, ctypes.byref(n))
+    return st, int(n.value)
+
+
+def mdnn_conv_bprop_data(dout, filt, in_hw, stride, pad, alpha=1.0, din=None, workspace=None, stream=None):
+    """dout (No,Ho,Wo,Nb), filt (Nc,Sk,Sk,No): contiguous fp32 device tensors; in_hw = (Hi, Wi)
+    of the forward input.  Returns din (Nc,Hi,Wi,Nb) enqueued on ``stream``.  ``workspace`` is a
+    uint8/float device tensor of at least mdnn_conv_bprop_data_workspace() bytes; one is allocated
+    with torch if none is given (allocation is the binding's, the library itself never allocates)."""
+    import torch
+
+    if not (dout.is_cuda and filt.is_cuda):
+        raise ValueError("mdnn_conv_bprop_data needs device tensors (no CPU path exists)")
+    if dout.dtype != torch.float32 or filt.dtype != torch.float32:
+        raise ValueError("fp32 only")
+    if not (dout.is_contiguous() and filt.is_contiguous()):
+        raise ValueError("tensors must be contiguous")
+    No, Ho, Wo, Nb = dout.shape
+    Nc, Sk, Sk2, No2 = filt.shape
+    Hi, Wi = in_hw
+    if No2 != No or Sk2 != Sk:
+        raise ValueError("filter shape does not match dout")
+    st, wo, ho = mdnn_out_dims(Wi, Hi, Sk, stride, pad)
+    if st != MDNN_OK:
+        raise MdnnError(st, "mdnn_out_dims")
+    if (wo, ho) != (Wo, Ho):
+        raise ValueError("dout spatial size does not match the forward geometry")
+    st, need = mdnn_conv_bprop_data_workspace(Nb, Wi, Hi, Nc, No, Sk, stride, pad)
+    if st != MDNN_OK:
+        raise MdnnError(st, "mdnn_conv_bprop_data_workspace")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dout.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    if din is None:
+        din = torch.empty((Nc, Hi, Wi, Nb), dtype=torch.float32, device=dout.device)
+    elif tuple(din.shape) != (Nc, Hi, Wi, Nb) or din.dtype != torch.float32 or not din.is_contiguous():
+        raise ValueError("din has the wrong shape / dtype / layout")
+    if stream is None:
+        stream = torch.cuda.current_stream(dout.device)
+    st = lib().mdnn_conv_bprop_data(dout.data_ptr(), filt.data_ptr(), din.data_ptr(),
+                                    workspace.data_ptr(), ws_bytes, Nb, Wi, Hi, Nc, No, Sk, stride, pad,
+                                    float(alpha), stream.cuda_stream or None)
+    if st != MDNN_OK:
+        raise MdnnError(st, "mdnn_conv_bprop_data")
+    return din
 
 
 def mdnn_mfma_peak_probe(sink, blocks, waves_per_block, iters, stream=None) -> int:

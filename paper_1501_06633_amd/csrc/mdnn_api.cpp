@@ -286,6 +286,86 @@ mdnn_status mdnn_conv_fprop(const float* in, const float* filt, float* out,
                                    stream, nullptr);
 }
 
+namespace {
+
+// Geometry of the forward convolution whose stride-1 run yields the data gradient.
+struct BpropPlan {
+    int       Hd, Wd;          // extent of the (dilated) output gradient the kernel reads
+    int       pad_t;           // Sk - 1 - pad
+    size_t    ft_bytes;        // flipped / transposed filter bank
+    size_t    d_offset;        // byte offset of the dilated gradient in the workspace (stride > 1)
+    size_t    total_bytes;
+};
+
+mdnn_status bprop_plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int pad, BpropPlan* b)
+{
+    Geometry g;
+    const mdnn_status gs = check_geometry(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &g);
+    if (gs != MDNN_OK) return gs;
+    if (pad > Sk - 1) return MDNN_EINVAL;      // would need a negative pad in the transposed problem
+    b->Hd = Hi + 2 * pad - Sk + 1;             // >= (Ho-1)*stride + 1; the surplus rows are zeros
+    b->Wd = Wi + 2 * pad - Sk + 1;
+    b->pad_t = Sk - 1 - pad;
+    b->ft_bytes = (size_t)g.filt_bytes;
+    b->d_offset = (b->ft_bytes + 255) & ~(size_t)255;
+    b->total_bytes = b->d_offset;
+    if (stride > 1) {
+        const int64_t d_bytes = 4 * (int64_t)No * b->Hd * b->Wd * Nb;
+        if (d_bytes >= kFourGiB) return MDNN_ETOOBIG;
+        b->total_bytes += (size_t)d_bytes;
+    }
+    return MDNN_OK;
+}
+
+}  // namespace
+
+mdnn_status mdnn_conv_bprop_data_workspace(int Nb, int Wi, int Hi, int Nc, int No,
+                                           int Sk, int stride, int pad, size_t* bytes)
+{
+    if (!bytes) return MDNN_ENULL;
+    BpropPlan b;
+    const mdnn_status s = bprop_plan(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &b);
+    if (s != MDNN_OK) return s;
+    *bytes = b.total_bytes;
+    return MDNN_OK;
+}
+
+mdnn_status mdnn_conv_bprop_data(const float* dout, const float* filt, float* din,
+                                 void* workspace, size_t workspace_bytes,
+                                 int Nb, int Wi, int Hi, int Nc, int No,
+                                 int Sk, int stride, int pad, float alpha, void* stream)
+{
+    if (!dout || !filt || !din || !workspace) return MDNN_ENULL;
+    BpropPlan b;
+    const mdnn_status bs = bprop_plan(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &b);
+    if (bs != MDNN_OK) return bs;
+    if (!std::isfinite(alpha)) return MDNN_EINVAL;
+    if (workspace_bytes < b.total_bytes) return MDNN_EINVAL;
+    if (((uintptr_t)dout | (uintptr_t)filt | (uintptr_t)din | (uintptr_t)workspace) & 15u) return MDNN_EALIGN;
+
+    Geometry g;
+    check_geometry(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &g);       // succeeded inside bprop_plan
+    float* ft = static_cast<float*>(workspace);
+    float* d  = reinterpret_cast<float*>(static_cast<char*>(workspace) + b.d_offset);
+
+    // the transposed problem: No input channels, Nc filters, stride 1, pad Sk-1-pad, image Hd x Wd
+    mdnn::ConvParams p;
+    int v = -1;
+    const mdnn_status ps = plan(Nb, b.Wd, b.Hd, No, Nc, Sk, 1, b.pad_t, nullptr, &p, &v);
+    if (ps != MDNN_OK) return ps;
+    if (p.Ho != Hi || p.Wo != Wi) return MDNN_EINVAL;              // cannot happen: (Hd + 2 pad_t - Sk) + 1 == Hi
+
+    if (mdnn::launch_flip_transpose(filt, ft, Nc, No, Sk * Sk, stream) != 0) return MDNN_ELAUNCH;
+    const float* src = dout;
+    if (stride > 1) {
+        if (mdnn::launch_dilate(dout, d, No, g.Ho, g.Wo, b.Hd, b.Wd, Nb, stride, stream) != 0) return MDNN_ELAUNCH;
+        src = d;
+    }
+    p.in = src;  p.filt = ft;  p.out = din;
+    p.alpha = alpha;
+    return mdnn::launch_variant(v, p, stream) == 0 ? MDNN_OK : MDNN_ELAUNCH;
+}
+
 mdnn_status mdnn_mfma_peak_probe(float* sink, int blocks, int waves_per_block, int iters,
                                  uint64_t* flops, void* stream)
 {

@@ -72,5 +72,10 @@ int launch_variant(int i, const ConvParams& p, void* stream);
 
 int launch_mfma_probe(float* sink, int blocks, int waves_per_block, int iters, void* stream);
 
+// Layout kernels of the data gradient (bprop_data.hip); return hipSuccess (0) or the HIP error code.
+int launch_flip_transpose(const float* filt, float* ft, int Nc, int No, int SkSk, void* stream);
+int launch_dilate(const float* dout, float* d, int No, int Ho, int Wo, int Hd, int Wd, int Nb, int stride,
+                  void* stream);
+
 }  // namespace mdnn
 #endif

@@ -33,7 +33,8 @@ def test_exports_every_declared_symbol(L):
     names = declared_functions()
     assert {"mdnn_conv_fprop", "mdnn_conv_fprop_variant", "mdnn_out_dims", "mdnn_conv_flops",
             "mdnn_status_string", "mdnn_variant_count", "mdnn_variant_name",
-            "mdnn_choose_variant", "mdnn_describe_launch", "mdnn_mfma_peak_probe"} <= set(names)
+            "mdnn_choose_variant", "mdnn_describe_launch", "mdnn_mfma_peak_probe",
+            "mdnn_conv_bprop_data", "mdnn_conv_bprop_data_workspace"} <= set(names)
     for n in names:
         assert hasattr(L, n), f"libmdnn.so does not export {n}"
 
@@ -135,6 +136,26 @@ def test_describe_launch(L):
     with pytest.raises(B.MdnnError):
         B.mdnn_describe_launch(8, 9, 9, 1, 4, 3, 1, 0, "nope")
     assert L.mdnn_describe_launch(8, 9, 9, 1, 4, 3, 1, 0, None, None, 0) == B.MDNN_ENULL
+
+
+def test_bprop_data_workspace_and_argument_checks(L):
+    # stride 1: only the rearranged filter bank (Nc*Sk*Sk*No floats), rounded up to 256 bytes
+    st, n = B.mdnn_conv_bprop_data_workspace(64, 56, 56, 256, 256, 3, 1, 1)
+    assert st == B.MDNN_OK and n == 256 * 9 * 256 * 4
+    # stride 4: plus the dilated gradient No x (Hi+2p-Sk+1)^2 x Nb
+    st, n = B.mdnn_conv_bprop_data_workspace(128, 227, 227, 3, 96, 11, 4, 0)
+    ft = 3 * 121 * 96 * 4
+    assert st == B.MDNN_OK and n == ((ft + 255) // 256) * 256 + 96 * 217 * 217 * 128 * 4
+    assert B.mdnn_conv_bprop_data_workspace(8, 8, 8, 2, 4, 3, 1, 3)[0] == B.MDNN_EINVAL     # pad > Sk - 1
+    assert B.mdnn_conv_bprop_data_workspace(8, 2, 2, 2, 4, 3, 1, 0)[0] == B.MDNN_EINVAL     # no output
+    assert L.mdnn_conv_bprop_data_workspace(8, 8, 8, 2, 4, 3, 1, 1, None) == B.MDNN_ENULL
+    args = (8, 8, 8, 2, 4, 3, 1, 1)
+    need = B.mdnn_conv_bprop_data_workspace(*args)[1]
+    call_b = lambda d=FAKE, f=FAKE, o=FAKE, w=FAKE, wb=need, a=1.0: L.mdnn_conv_bprop_data(d, f, o, w, wb, *args, a, None)
+    assert call_b(d=None) == B.MDNN_ENULL and call_b(w=None) == B.MDNN_ENULL
+    assert call_b(wb=need - 1) == B.MDNN_EINVAL
+    assert call_b(a=float("nan")) == B.MDNN_EINVAL
+    assert call_b(w=FAKE + 4) == B.MDNN_EALIGN
 
 
 def test_status_strings(L):

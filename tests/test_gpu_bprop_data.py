@@ -1,0 +1,142 @@
+"""GPU parity of the data gradient (BPROP w.r.t. the input) against the oracle,
+through the C ABI.  Same acceptance bound as the forward path: per element
+|gpu - oracle| <= 1e-4 * |alpha| * A (A = sum of |products|), exactly 0 where
+A == 0, plus the 2e-5 regression bound; integer data bit for bit."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_1501_06633_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+LOOSE, TIGHT = 1e-4, 2e-5
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_1501_06633_amd import binding as B
+    B.lib()
+    import oracle
+    oracle.build(force=False)
+    return torch, B, oracle
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def make_grad(layer, oracle, integer=False):
+    """Seeded output gradient of the layer's forward shape, and its filters."""
+    Wo, Ho = oracle.out_dims(layer.Wi, layer.Hi, layer.Sk, layer.stride, layer.pad)
+    rng = np.random.Generator(np.random.PCG64(layer.seed + 31337))
+    shape = (layer.No, Ho, Wo, layer.Nb)
+    if integer:
+        dout = rng.integers(-4, 5, size=shape).astype(np.float32)
+        filt = rng.integers(-4, 5, size=(layer.Nc, layer.Sk, layer.Sk, layer.No)).astype(np.float32)
+    else:
+        dout = rng.standard_normal(size=shape, dtype=np.float32)
+        _, filt = W.make_inputs(layer)
+    return dout, filt
+
+
+def run_gpu(env, layer, dout, filt):
+    torch, B, _ = env
+    out = B.mdnn_conv_bprop_data(torch.from_numpy(dout).cuda(), torch.from_numpy(filt).cuda(),
+                                 (layer.Hi, layer.Wi), layer.stride, layer.pad, layer.alpha)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def check(got, want, absum, alpha, what):
+    err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    scale = abs(alpha) * absum
+    zero = scale == 0
+    assert (got[zero] == 0).all(), f"{what}: non-zero gradient where every product is zero"
+    ratio = np.zeros_like(err)
+    np.divide(err, scale, out=ratio, where=~zero)
+    worst = float(ratio.max()) if ratio.size else 0.0
+    say(f"    {what}: max |err|/(|alpha| A) = {worst:.3e} over {got.size} elements")
+    assert np.isfinite(got).all()
+    assert worst <= LOOSE and worst <= TIGHT, f"{what}: bound exceeded ({worst:.3e})"
+
+
+@pytest.mark.parametrize("name", ["tiny", "conv2", "conv3", "vgg"])
+def test_layer_gradient_matches_oracle_everywhere(env, name):
+    """Stride-1 layers at full size, every element of din."""
+    _, B, oracle = env
+    L = W.LAYERS[name]
+    say(f"[bprop] layer={name} dims={L.dims()}")
+    dout, filt = make_grad(L, oracle)
+    got = run_gpu(env, L, dout, filt)
+    want, absum = oracle.conv_bprop_data(dout, filt, (L.Hi, L.Wi), L.stride, L.pad, L.alpha)
+    check(got, want, absum, L.alpha, name)
+
+
+def test_strided_first_layer_gradient(env):
+    """conv1 (stride 4, 11x11): the gradient goes through the dilated path; whole tensor."""
+    _, B, oracle = env
+    L = W.LAYERS["conv1"]
+    say(f"[bprop] layer=conv1 dims={L.dims()}")
+    dout, filt = make_grad(L, oracle)
+    got = run_gpu(env, L, dout, filt)
+    want, absum = oracle.conv_bprop_data(dout, filt, (L.Hi, L.Wi), L.stride, L.pad, L.alpha)
+    check(got, want, absum, L.alpha, "conv1")
+
+
+ODD = [
+    # name             Nb  Hi  Wi  Nc  No  Sk st pad alpha
+    ("ragged",         12, 11,  9,  5, 36, 3, 1, 1, 0.5),
+    ("scalar_path",     7, 10, 11,  3, 37, 3, 2, 1, 1.5),    # Nb, No, Nc not multiples of 4
+    ("stride2_unread",  8,  8,  8,  4, 12, 3, 2, 0, 1.0),    # last row / column never read: gradient 0
+    ("stride3_nonsq",  20,  9, 14,  6, 40, 4, 3, 1, 0.25),
+    ("stride_gt_sk",    8, 12,  9,  4,  8, 3, 4, 1, 1.0),    # gaps between windows
+    ("one_by_one",     16,  6,  7, 40, 24, 1, 1, 0, -2.0),
+    ("pad_max",         8,  6,  6,  3, 12, 3, 1, 2, 1.0),    # pad = Sk - 1
+    ("one_window",      4,  5,  5,  4,  8, 5, 1, 0, 1.0),
+    ("many_tiles",     32, 15, 13, 20, 200, 3, 1, 1, 1.0),
+]
+
+
+@pytest.mark.parametrize("case", ODD, ids=[c[0] for c in ODD])
+def test_odd_shapes_integer_bitwise(env, case):
+    _, B, oracle = env
+    name, Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha = case
+    L = W.custom(name, Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha, seed=W.SEED_BASE + 200 + len(name))
+    say(f"[bprop-odd] case={name} dims={L.dims()}")
+    dout, filt = make_grad(L, oracle, integer=True)
+    got = run_gpu(env, L, dout, filt)
+    want = oracle.conv_bprop_data(dout, filt, (Hi, Wi), stride, pad, alpha, want_abs=False)
+    np.testing.assert_array_equal(got, want)
+
+
+def test_is_the_adjoint_of_the_gpu_forward(env):
+    """<fprop(x), g> == <x, bprop_data(g)> with both sides on the GPU, integer data (exact)."""
+    torch, B, oracle = env
+    L = W.custom("adj", 16, 12, 10, 8, 24, 3, 2, 1, 0.5)
+    x, filt = W.make_int_inputs(L)
+    g, _ = make_grad(L, oracle, integer=True)
+    d_x, d_f, d_g = (torch.from_numpy(a).cuda() for a in (x, filt, g))
+    y = B.mdnn_conv_fprop(d_x, d_f, L.stride, L.pad, L.alpha)
+    dx = B.mdnn_conv_bprop_data(d_g, d_f, (L.Hi, L.Wi), L.stride, L.pad, L.alpha)
+    torch.cuda.synchronize()
+    assert float((y.double() * d_g.double()).sum()) == float((d_x.double() * dx.double()).sum())
+
+
+def test_caller_workspace_and_overwrite(env):
+    torch, B, oracle = env
+    L = W.custom("ws", 8, 9, 9, 4, 16, 3, 2, 1, 1.0)
+    dout, filt = make_grad(L, oracle, integer=True)
+    st, need = B.mdnn_conv_bprop_data_workspace(L.Nb, L.Wi, L.Hi, L.Nc, L.No, L.Sk, L.stride, L.pad)
+    assert st == 0
+    ws = torch.full((need // 4 + 8,), float("nan"), device="cuda")          # garbage in, larger than needed
+    din = torch.full((L.Nc, L.Hi, L.Wi, L.Nb), float("nan"), device="cuda")
+    B.mdnn_conv_bprop_data(torch.from_numpy(dout).cuda(), torch.from_numpy(filt).cuda(), (L.Hi, L.Wi),
+                           L.stride, L.pad, L.alpha, din=din, workspace=ws)
+    torch.cuda.synchronize()
+    want = oracle.conv_bprop_data(dout, filt, (L.Hi, L.Wi), L.stride, L.pad, L.alpha, want_abs=False)
+    np.testing.assert_array_equal(din.cpu().numpy(), want)
