@@ -48,6 +48,11 @@ def _load():
     lib.mdnn_oracle_conv_fprop.restype = i
     lib.mdnn_oracle_conv_bprop_data.argtypes = [p, p, p, p, i, i, i, i, i, i, i, i, f, i]
     lib.mdnn_oracle_conv_bprop_data.restype = i
+    lib.mdnn_oracle_conv_bprop_filter.argtypes = [p, p, p, p, i, i, i, i, i, i, i, i, f, i]
+    lib.mdnn_oracle_conv_bprop_filter.restype = i
+    lib.mdnn_oracle_conv_bprop_filter_points.argtypes = [p, p, p, ctypes.c_int64, p, p,
+                                                         i, i, i, i, i, i, i, i, f]
+    lib.mdnn_oracle_conv_bprop_filter_points.restype = i
     lib.mdnn_oracle_conv_fprop_points.argtypes = [p, p, p, ctypes.c_int64, p, p,
                                                   i, i, i, i, i, i, i, i, f]
     lib.mdnn_oracle_conv_fprop_points.restype = i
@@ -141,3 +146,48 @@ def conv_bprop_data(dout, filt, in_hw, stride, pad, alpha, want_abs=True, nthrea
     if rc:
         raise ValueError("oracle rejected the arguments")
     return (din, ab) if want_abs else din
+
+
+def conv_bprop_filter(inp, dout, Sk, stride, pad, alpha, want_abs=True, nthreads=0):
+    """inp (Nc,Hi,Wi,Nb) f32, dout (No,Ho,Wo,Nb) f32 -> dfilt (Nc,Sk,Sk,No) f32 and, when
+    ``want_abs``, the per-element sum of |products| in float64."""
+    Nc, Hi, Wi, Nb = inp.shape
+    No, Ho, Wo, Nb2 = dout.shape
+    if Nb2 != Nb:
+        raise ValueError("batch sizes differ")
+    _check(inp, inp.shape, "inp")
+    _check(dout, dout.shape, "dout")
+    if out_dims(Wi, Hi, Sk, stride, pad) != (Wo, Ho):
+        raise ValueError("dout spatial size does not match the forward geometry")
+    dfilt = np.empty((Nc, Sk, Sk, No), dtype=np.float32)
+    ab = np.empty((Nc, Sk, Sk, No), dtype=np.float64) if want_abs else None
+    rc = _load().mdnn_oracle_conv_bprop_filter(
+        inp.ctypes.data, dout.ctypes.data, dfilt.ctypes.data,
+        ab.ctypes.data if ab is not None else None,
+        Nb, Wi, Hi, Nc, No, Sk, stride, pad, float(alpha), int(nthreads))
+    if rc:
+        raise ValueError("oracle rejected the arguments")
+    return (dfilt, ab) if want_abs else dfilt
+
+
+def conv_bprop_filter_points(inp, dout, idx, Sk, stride, pad, alpha):
+    """The filter gradient at the (c,ky,kx,o) rows of ``idx`` only.
+    Returns (values float32[npts], abs_sums float64[npts])."""
+    Nc, Hi, Wi, Nb = inp.shape
+    No = dout.shape[0]
+    _check(inp, inp.shape, "inp")
+    _check(dout, dout.shape, "dout")
+    if out_dims(Wi, Hi, Sk, stride, pad) != (dout.shape[2], dout.shape[1]) or dout.shape[3] != Nb:
+        raise ValueError("dout does not match the forward geometry")
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    if idx.ndim != 2 or idx.shape[1] != 4:
+        raise ValueError("idx must be (npts, 4)")
+    vals = np.empty(idx.shape[0], dtype=np.float32)
+    ab = np.empty(idx.shape[0], dtype=np.float64)
+    rc = _load().mdnn_oracle_conv_bprop_filter_points(
+        inp.ctypes.data, dout.ctypes.data, idx.ctypes.data, idx.shape[0],
+        vals.ctypes.data, ab.ctypes.data,
+        Nb, Wi, Hi, Nc, No, Sk, stride, pad, float(alpha))
+    if rc:
+        raise ValueError("oracle rejected the arguments (index out of range?)")
+    return vals, ab

@@ -35,7 +35,12 @@
  * conjectures to work the same way (abstract, Section 3.5), is written out too:
  * it is the adjoint of the map in -> out above, scaled by alpha.  Its pins are
  * the adjoint identity against the forward function, a scatter-add brute force,
- * torch's transposed convolution in float64 and delta tests.
+ * torch's transposed convolution in float64 and delta tests.  So is the filter
+ * gradient (BPROP with respect to the weights): the adjoint of the map
+ * filt -> out.  Its pins: the same identity on the filter side (basis filters
+ * included, which fixes every element separately), an accumulation over output
+ * pixels of patch x gradient outer products in numpy, torch autograd in float64,
+ * deltas, and planted-mistake tests.
  *
  * Pins (tests/test_oracle_*.py, CPU only): brute-force im2col x GEMM in numpy
  * float64, the 1x1/stride-1 = plain matrix product identity, delta filters,
@@ -275,4 +280,105 @@ int mdnn_oracle_conv_bprop_data(const float* dout, const float* filt, float* din
         free(A);
     }
     return failed;
+}
+
+/*
+ * Filter gradient of the convolution above (BPROP w.r.t. the weights):
+ *   dfilt[c][ky][kx][o] = alpha * sum_{y,x,n} in[c][y*stride-pad+ky][x*stride-pad+kx][n] * dout[o][y][x][n]
+ * with apron reads contributing 0 -- every forward term in which filt[c][ky][kx][o]
+ * took part, weighted by the gradient of the output it went into.  dfilt has the
+ * layout and size of `filt`.  abs_sum as in the forward function.
+ * Loops: c, ky, kx, o, y, x, n (n innermost), OpenMP over c only.
+ */
+int mdnn_oracle_conv_bprop_filter(const float* in, const float* dout, float* dfilt,
+                                  double* abs_sum,
+                                  int Nb, int Wi, int Hi, int Nc, int No,
+                                  int Sk, int stride, int pad, float alpha,
+                                  int nthreads)
+{
+    int Wo, Ho;
+    if (!in || !dout || !dfilt) return 1;
+    if (Nb < 1 || Nc < 1 || No < 1) return 1;
+    if (mdnn_oracle_out_dims(Wi, Hi, Sk, stride, pad, &Wo, &Ho)) return 1;
+#ifdef _OPENMP
+    if (nthreads <= 0) nthreads = omp_get_max_threads();
+#else
+    nthreads = 1;
+#endif
+
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+    for (int c = 0; c < Nc; ++c) {
+        for (int ky = 0; ky < Sk; ++ky) {
+            for (int kx = 0; kx < Sk; ++kx) {
+                for (int o = 0; o < No; ++o) {
+                    double S = 0.0, A = 0.0;
+                    for (int y = 0; y < Ho; ++y) {
+                        int iy = y * stride - pad + ky;
+                        if (iy < 0 || iy >= Hi) continue;       /* zero apron */
+                        for (int x = 0; x < Wo; ++x) {
+                            int ix = x * stride - pad + kx;
+                            if (ix < 0 || ix >= Wi) continue;
+                            const float* a = in + (((size_t)c * Hi + iy) * Wi + ix) * (size_t)Nb;
+                            const float* g = dout + (((size_t)o * Ho + y) * Wo + x) * (size_t)Nb;
+                            for (int n = 0; n < Nb; ++n) {
+                                double p = (double)a[n] * (double)g[n];
+                                S += p;
+                                A += fabs(p);
+                            }
+                        }
+                    }
+                    size_t e = (((size_t)c * Sk + ky) * Sk + kx) * (size_t)No + o;
+                    dfilt[e] = (float)((double)alpha * S);
+                    if (abs_sum) abs_sum[e] = A;
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/*
+ * The same definition at selected filter elements only: idx holds npts rows
+ * (c, ky, kx, o).  For layers whose whole gradient is too slow to evaluate here.
+ * Returns 0, or 1 when an argument or an index is out of range.
+ */
+int mdnn_oracle_conv_bprop_filter_points(const float* in, const float* dout,
+                                         const int* idx, long long npts,
+                                         float* val, double* abs_val,
+                                         int Nb, int Wi, int Hi, int Nc, int No,
+                                         int Sk, int stride, int pad, float alpha)
+{
+    int Wo, Ho;
+    if (!in || !dout || !idx || !val || npts < 0) return 1;
+    if (Nb < 1 || Nc < 1 || No < 1) return 1;
+    if (mdnn_oracle_out_dims(Wi, Hi, Sk, stride, pad, &Wo, &Ho)) return 1;
+    int bad = 0;
+
+#pragma omp parallel for schedule(dynamic, 4) reduction(|:bad)
+    for (long long i = 0; i < npts; ++i) {
+        int c = idx[4 * i + 0], ky = idx[4 * i + 1], kx = idx[4 * i + 2], o = idx[4 * i + 3];
+        if (c < 0 || c >= Nc || ky < 0 || ky >= Sk || kx < 0 || kx >= Sk || o < 0 || o >= No) {
+            bad |= 1;
+            continue;
+        }
+        double S = 0.0, A = 0.0;
+        for (int y = 0; y < Ho; ++y) {
+            int iy = y * stride - pad + ky;
+            if (iy < 0 || iy >= Hi) continue;
+            for (int x = 0; x < Wo; ++x) {
+                int ix = x * stride - pad + kx;
+                if (ix < 0 || ix >= Wi) continue;
+                const float* a = in + (((size_t)c * Hi + iy) * Wi + ix) * (size_t)Nb;
+                const float* g = dout + (((size_t)o * Ho + y) * Wo + x) * (size_t)Nb;
+                for (int n = 0; n < Nb; ++n) {
+                    double p = (double)a[n] * (double)g[n];
+                    S += p;
+                    A += fabs(p);
+                }
+            }
+        }
+        val[i] = (float)((double)alpha * S);
+        if (abs_val) abs_val[i] = A;
+    }
+    return bad;
 }
