@@ -126,6 +126,37 @@ mdnn_status mdnn_conv_bprop_data(const float* dout, const float* filt, float* di
                                  int Sk, int stride, int pad, float alpha, void* stream);
 
 /*
+ * Filter gradient (BPROP with respect to the weights), the other half of what
+ * the paper leaves as a conjecture (abstract, Section 3.5).  It is the
+ * per-coordinate patch x filter-matrix product of Section 3 turned round: the
+ * K x No gradient of the filter matrix is the sum, over all output coordinates
+ * and images, of patch column times output-gradient row, computed as one
+ * implicit GEMM on the matrix cores with the patch gathered as in Section 3.2.
+ *
+ *   in    device, fp32, [Nc][Hi][Wi][Nb]   the forward input
+ *   dout  device, fp32, [No][Ho][Wo][Nb]   gradient w.r.t. the forward output
+ *   dfilt device, fp32, [Nc][Sk][Sk][No]   fully overwritten
+ *
+ *   dfilt[c][ky][kx][o] = alpha * sum_{y,x,n} in[c][y*stride-pad+ky][x*stride-pad+kx][n] * dout[o][y][x][n]
+ *   (apron reads are 0).
+ *
+ * The dimension arguments are those of the FORWARD call; any pad is accepted.
+ * `workspace` is device memory of at least the size
+ * mdnn_conv_bprop_filter_workspace() reports (16-byte aligned): the contraction
+ * is cut into ranges so that the launch fills the chip, every range leaves a
+ * partial gradient there, and a second kernel adds them in a fixed order (the
+ * result is deterministic).  It may be reused or freed once the stream has
+ * passed this call.  Same stream, ownership and error rules as mdnn_conv_fprop;
+ * in and dout must each be smaller than 2^32 bytes (MDNN_ETOOBIG).
+ */
+mdnn_status mdnn_conv_bprop_filter_workspace(int Nb, int Wi, int Hi, int Nc, int No,
+                                             int Sk, int stride, int pad, size_t* bytes);
+mdnn_status mdnn_conv_bprop_filter(const float* in, const float* dout, float* dfilt,
+                                   void* workspace, size_t workspace_bytes,
+                                   int Nb, int Wi, int Hi, int Nc, int No,
+                                   int Sk, int stride, int pad, float alpha, void* stream);
+
+/*
  * Describe, as one line of text, how a problem would be launched: variant, tile
  * shape, number of tiles, how the last partial round of tiles is cut into
  * smaller pieces (the other block sizes Section 3.4 proposes), grid and LDS

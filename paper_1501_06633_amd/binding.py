@@ -55,6 +55,10 @@ def lib() -> ctypes.CDLL:
     L.mdnn_conv_bprop_data_workspace.restype = i
     L.mdnn_conv_bprop_data.argtypes = [p, p, p, p, ctypes.c_size_t, i, i, i, i, i, i, i, i, f, p]
     L.mdnn_conv_bprop_data.restype = i
+    L.mdnn_conv_bprop_filter_workspace.argtypes = [i] * 8 + [ctypes.POINTER(ctypes.c_size_t)]
+    L.mdnn_conv_bprop_filter_workspace.restype = i
+    L.mdnn_conv_bprop_filter.argtypes = [p, p, p, p, ctypes.c_size_t, i, i, i, i, i, i, i, i, f, p]
+    L.mdnn_conv_bprop_filter.restype = i
     L.mdnn_mfma_peak_probe.argtypes = [p, i, i, i, ctypes.POINTER(ctypes.c_uint64), p]
     L.mdnn_mfma_peak_probe.restype = i
     _lib = L
@@ -192,6 +196,55 @@ def mdnn_conv_bprop_data(dout, filt, in_hw, stride, pad, alpha=1.0, din=None, wo
     if st != MDNN_OK:
         raise MdnnError(st, "mdnn_conv_bprop_data")
     return din
+
+
+def mdnn_conv_bprop_filter_workspace(Nb, Wi, Hi, Nc, No, Sk, stride, pad):
+    """-> (status, bytes)"""
+    n = ctypes.c_size_t(0)
+    st = lib().mdnn_conv_bprop_filter_workspace(Nb, Wi, Hi, Nc, No, Sk, stride, pad, ctypes.byref(n))
+    return st, int(n.value)
+
+
+def mdnn_conv_bprop_filter(inp, dout, Sk, stride, pad, alpha=1.0, dfilt=None, workspace=None, stream=None):
+    """inp (Nc,Hi,Wi,Nb), dout (No,Ho,Wo,Nb): contiguous fp32 device tensors.  Returns dfilt
+    (Nc,Sk,Sk,No) enqueued on ``stream``.  ``workspace`` is a device tensor of at least
+    mdnn_conv_bprop_filter_workspace() bytes; one is allocated with torch if none is given
+    (allocation is the binding's, the library itself never allocates)."""
+    import torch
+
+    if not (inp.is_cuda and dout.is_cuda):
+        raise ValueError("mdnn_conv_bprop_filter needs device tensors (no CPU path exists)")
+    if inp.dtype != torch.float32 or dout.dtype != torch.float32:
+        raise ValueError("fp32 only")
+    if not (inp.is_contiguous() and dout.is_contiguous()):
+        raise ValueError("tensors must be contiguous")
+    Nc, Hi, Wi, Nb = inp.shape
+    No, Ho, Wo, Nb2 = dout.shape
+    if Nb2 != Nb:
+        raise ValueError("batch sizes differ")
+    st, wo, ho = mdnn_out_dims(Wi, Hi, Sk, stride, pad)
+    if st != MDNN_OK:
+        raise MdnnError(st, "mdnn_out_dims")
+    if (wo, ho) != (Wo, Ho):
+        raise ValueError("dout spatial size does not match the forward geometry")
+    st, need = mdnn_conv_bprop_filter_workspace(Nb, Wi, Hi, Nc, No, Sk, stride, pad)
+    if st != MDNN_OK:
+        raise MdnnError(st, "mdnn_conv_bprop_filter_workspace")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=inp.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    if dfilt is None:
+        dfilt = torch.empty((Nc, Sk, Sk, No), dtype=torch.float32, device=inp.device)
+    elif tuple(dfilt.shape) != (Nc, Sk, Sk, No) or dfilt.dtype != torch.float32 or not dfilt.is_contiguous():
+        raise ValueError("dfilt has the wrong shape / dtype / layout")
+    if stream is None:
+        stream = torch.cuda.current_stream(inp.device)
+    st = lib().mdnn_conv_bprop_filter(inp.data_ptr(), dout.data_ptr(), dfilt.data_ptr(),
+                                      workspace.data_ptr(), ws_bytes, Nb, Wi, Hi, Nc, No, Sk, stride, pad,
+                                      float(alpha), stream.cuda_stream or None)
+    if st != MDNN_OK:
+        raise MdnnError(st, "mdnn_conv_bprop_filter")
+    return dfilt
 
 
 def mdnn_mfma_peak_probe(sink, blocks, waves_per_block, iters, stream=None) -> int:

@@ -9,8 +9,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmdnn.so")
 SOURCES = [os.path.join(CSRC, "conv_fprop.hip"), os.path.join(CSRC, "bprop_data.hip"),
-           os.path.join(CSRC, "mdnn_api.cpp")]
-HEADERS = [os.path.join(CSRC, "mdnn_internal.h"), os.path.join(ROOT, "include", "mdnn.h")]
+           os.path.join(CSRC, "bprop_filter.hip"), os.path.join(CSRC, "mdnn_api.cpp")]
+HEADERS = [os.path.join(CSRC, "mdnn_internal.h"), os.path.join(CSRC, "gfx950_util.h"), os.path.join(ROOT, "include", "mdnn.h")]
 
 # Packed-FP32 VALU forms are switched off for all device code; the host pass of
 # hipcc does not know the feature and says so (harmless).

@@ -1,6 +1,7 @@
 // Host side of the C ABI: argument checks, geometry, the complexity formula,
 // tile-variant choice.  No HIP call happens in this file; launches go through
 // mdnn::launch_variant().
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -317,7 +318,80 @@ mdnn_status bprop_plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int strid
     return MDNN_OK;
 }
 
+// Filter gradient: 128 x 128 tiles of the K x No result, the contraction over m = (y,x,n) cut
+// into `splits` ranges so that the launch fills the chip.  Cost of a choice, in slabs of 16 m:
+// rounds of 512 co-resident workgroups (two per compute unit) times a workgroup's slabs plus a
+// fixed start-up/store share.
+mdnn_status filter_grad_plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int pad,
+                             mdnn::FilterGradParams* f, size_t* workspace_bytes)
+{
+    Geometry g;
+    const mdnn_status gs = check_geometry(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &g);
+    if (gs != MDNN_OK) return gs;
+    mdnn::FilterGradParams p;
+    p.in = nullptr;  p.dout = nullptr;  p.part = nullptr;
+    p.Nb = Nb;  p.Wi = Wi;  p.Hi = Hi;  p.Nc = Nc;  p.No = No;
+    p.Sk = Sk;  p.stride = stride;  p.pad = pad;
+    p.Wo = g.Wo;  p.Ho = g.Ho;
+    p.K = (int)g.K;  p.SkSk = Sk * Sk;  p.M = (int)g.M;
+    division_magic((uint32_t)p.SkSk, &p.sksk_magic, &p.sksk_shift);
+    division_magic((uint32_t)Sk, &p.sk_magic, &p.sk_shift);
+    division_magic((uint32_t)Nb, &p.nb_magic, &p.nb_shift);
+    division_magic((uint32_t)g.Wo, &p.wo_magic, &p.wo_shift);
+    p.n_otiles = div_up(No, 128);
+    const int64_t n_tiles = (int64_t)div_up(g.K, 128) * p.n_otiles;
+    if (n_tiles > ((int64_t)1 << 24)) return MDNN_ETOOBIG;
+    p.n_tiles = (int)n_tiles;
+
+    const int64_t slabs = (g.M + 15) / 16;
+    const int64_t kSlots = 512, kFixed = 24, kMinSlabs = 8;
+    int64_t best_s = 1, best_cost = -1;
+    const int64_t s_max = std::min<int64_t>(std::max<int64_t>(1, slabs / kMinSlabs), 4096);
+    for (int64_t s = 1; s <= s_max; ++s) {
+        const int64_t per   = (slabs + s - 1) / s;
+        const int64_t real  = (slabs + per - 1) / per;             // ranges actually needed
+        const int64_t cost  = ((n_tiles * real + kSlots - 1) / kSlots) * (per + kFixed);
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_s = real; }
+        if (n_tiles * s > 8 * kSlots) break;
+    }
+    p.m_per_split = (int)(((slabs + best_s - 1) / best_s) * 16);
+    p.splits = (int)((g.M + p.m_per_split - 1) / p.m_per_split);
+    p.per_xcd = div_up((int64_t)p.n_tiles * p.splits, 8);
+    p.vec = (Nb % 4 == 0) ? 1 : 0;
+    p.uniform = (Nb % 16 == 0) ? 1 : 0;
+    p.in_bytes = (uint32_t)g.in_bytes;
+    p.dout_bytes = (uint32_t)g.out_bytes;
+    *f = p;
+    *workspace_bytes = (size_t)p.splits * (size_t)g.K * (size_t)No * sizeof(float);
+    return MDNN_OK;
+}
+
 }  // namespace
+
+mdnn_status mdnn_conv_bprop_filter_workspace(int Nb, int Wi, int Hi, int Nc, int No,
+                                             int Sk, int stride, int pad, size_t* bytes)
+{
+    if (!bytes) return MDNN_ENULL;
+    mdnn::FilterGradParams f;
+    return filter_grad_plan(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &f, bytes);
+}
+
+mdnn_status mdnn_conv_bprop_filter(const float* in, const float* dout, float* dfilt,
+                                   void* workspace, size_t workspace_bytes,
+                                   int Nb, int Wi, int Hi, int Nc, int No,
+                                   int Sk, int stride, int pad, float alpha, void* stream)
+{
+    if (!in || !dout || !dfilt || !workspace) return MDNN_ENULL;
+    mdnn::FilterGradParams f;
+    size_t need = 0;
+    const mdnn_status fs = filter_grad_plan(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &f, &need);
+    if (fs != MDNN_OK) return fs;
+    if (!std::isfinite(alpha)) return MDNN_EINVAL;
+    if (workspace_bytes < need) return MDNN_EINVAL;
+    if (((uintptr_t)in | (uintptr_t)dout | (uintptr_t)dfilt | (uintptr_t)workspace) & 15u) return MDNN_EALIGN;
+    f.in = in;  f.dout = dout;  f.part = static_cast<float*>(workspace);
+    return mdnn::launch_bprop_filter(f, dfilt, alpha, stream) == 0 ? MDNN_OK : MDNN_ELAUNCH;
+}
 
 mdnn_status mdnn_conv_bprop_data_workspace(int Nb, int Wi, int Hi, int Nc, int No,
                                            int Sk, int stride, int pad, size_t* bytes)

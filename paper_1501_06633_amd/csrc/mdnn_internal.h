@@ -77,5 +77,28 @@ int launch_flip_transpose(const float* filt, float* ft, int Nc, int No, int SkSk
 int launch_dilate(const float* dout, float* d, int No, int Ho, int Wo, int Hd, int Wd, int Nb, int stride,
                   void* stream);
 
+// Filter gradient (bprop_filter.hip): everything a workgroup needs.
+struct FilterGradParams {
+    const float* in;
+    const float* dout;
+    float*       part;       // workspace: [splits][K][No] partial gradients
+    int Nb, Wi, Hi, Nc, No, Sk, stride, pad;
+    int Wo, Ho;
+    int K, SkSk, M;
+    uint32_t sksk_magic, sksk_shift, sk_magic, sk_shift;
+    uint32_t nb_magic, nb_shift, wo_magic, wo_shift;
+    int n_otiles;            // 128-wide tiles along No
+    int n_tiles;             // tiles of the K x No gradient
+    int splits;              // ranges the contraction index m is cut into
+    int m_per_split;         // multiple of 16
+    int per_xcd;             // ceil(n_tiles * splits / 8)
+    int vec;                 // 1: 16-byte copies (Nb % 4 == 0)
+    int uniform;             // 1: Nb % 16 == 0, a slab of 16 m never straddles output coordinates
+    uint32_t in_bytes, dout_bytes;
+};
+
+// Enqueue the partial-gradient kernel and the kernel that sums the partials into dfilt.
+int launch_bprop_filter(const FilterGradParams& p, float* dfilt, float alpha, void* stream);
+
 }  // namespace mdnn
 #endif
