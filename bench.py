@@ -128,6 +128,9 @@ def main():
                     help="also time the data gradient (BPROP w.r.t. the input, computed by the FPROP kernels on "
                          "the turned-over filter bank) of the five layers; each call includes the filter "
                          "rearrangement and, for stride > 1, the dilation of the output gradient")
+    ap.add_argument("--bprop-filter", action="store_true",
+                    help="also time the filter gradient (BPROP w.r.t. the weights) of the five layers; each call "
+                         "is the partial-gradient kernel plus the kernel that sums the partials")
     ap.add_argument("--sgemm", action="store_true",
                     help="time the 1x1 / stride-1 special case, which is a plain SGEMM (the calibration the "
                          "paper's conclusion leans on), next to the vendor library's fp32 matmul")
@@ -295,6 +298,40 @@ def main():
             log(f"[bench] bprop-data {name:6s} {ms:9.5f} ms {rows[name]['tflops']:8.3f} TFLOP/s "
                 f"({100 * rows[name]['frac_peak']:.1f}% of peak, required FLOPs) stride={Lb.stride}")
         result["bprop_data"] = rows
+
+    if args.bprop_filter:
+        rows = {}
+        for name in W.ORDER:
+            Lb = W.LAYERS[name]
+            st, Wo, Ho = B.mdnn_out_dims(Lb.Wi, Lb.Hi, Lb.Sk, Lb.stride, Lb.pad)
+            inp, _ = W.make_inputs(Lb)
+            d_in = torch.from_numpy(inp).cuda()
+            d_g = torch.randn((Lb.No, Ho, Wo, Lb.Nb), device="cuda")
+            dfilt = torch.empty((Lb.Nc, Lb.Sk, Lb.Sk, Lb.No), device="cuda")
+            st, need = B.mdnn_conv_bprop_filter_workspace(Lb.Nb, Lb.Wi, Lb.Hi, Lb.Nc, Lb.No, Lb.Sk, Lb.stride, Lb.pad)
+            ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+
+            def launch(n):
+                for _ in range(n):
+                    B.mdnn_conv_bprop_filter(d_in, d_g, Lb.Sk, Lb.stride, Lb.pad, Lb.alpha, dfilt=dfilt, workspace=ws)
+            launch(5)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); launch(20); e1.record(); torch.cuda.synchronize()
+            per = e0.elapsed_time(e1) / 20
+            launch(int(WARM_MS_FLOOR / max(per, 1e-3)) + 1)
+            torch.cuda.synchronize()
+            steps = {"tiny": 200, "conv1": 100, "conv2": 50, "conv3": 100, "vgg": 30}[name]
+            e0.record(); launch(steps); e1.record(); torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / steps
+            # required work: every forward multiply-add has one counterpart in the gradient
+            fl = B.mdnn_conv_flops(Lb.Nb, Wo, Ho, Lb.Nc, Lb.No, Lb.Sk)
+            rows[name] = {"ms": round(ms, 5), "tflops": round(fl / ms / 1e9, 3),
+                          "frac_peak": round(fl / ms / 1e9 / PEAK_FP32_MATRIX_TFLOPS, 4),
+                          "workspace_bytes": need}
+            log(f"[bench] bprop-filter {name:6s} {ms:9.5f} ms {rows[name]['tflops']:8.3f} TFLOP/s "
+                f"({100 * rows[name]['frac_peak']:.1f}% of peak, required FLOPs) workspace {need / 1e6:.1f} MB")
+        result["bprop_filter"] = rows
 
     if args.sgemm:
         # out (No x M) = filt^T (No x K) . in (K x M) with M = Hi*Wi*Nb: a 1x1 convolution
