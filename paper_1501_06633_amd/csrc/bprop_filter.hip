@@ -42,7 +42,6 @@ namespace mdnn {
 namespace {
 
 constexpr int kTileK     = 128;   // rows of dfilt (k) per workgroup
-constexpr int kTileO     = 128;   // columns of dfilt (o) per workgroup
 constexpr int kSlabM     = 16;    // m per slab and row
 constexpr int kRowBytes  = kSlabM * 4;
 constexpr int kOperBytes = 128 * kRowBytes;       // one operand's slab
@@ -51,13 +50,20 @@ constexpr int kStageBytes = 2 * kOperBytes;
 // VW: floats per global -> LDS copy (4 needs Nb % 4 == 0).  UNIFORM: Nb % 16 == 0,
 // so the 16 m of a slab share one output coordinate and the walk over
 // coordinates is scalar work done once per coordinate instead of per copy.
+// WK x (4/WK) waves, each owning RA x RB MFMA blocks: WK*RA*32 = 128 rows k and
+// (4/WK)*RB*32 <= 128 columns o (Section 3.4's other block sizes, for layers with
+// few filters).  The G slab in LDS always has 128 rows; a narrower tile leaves
+// the surplus rows out of range (zero-filled, never read).
 //
 // The body is a device function, not the kernel itself: the host pass checks a
 // kernel's body against the host's idea of the target and rejects the 16-byte
 // form of the global -> LDS copy there.
-template <int VW, bool UNIFORM, int NS>
+template <int VW, bool UNIFORM, int NS, int WK, int RA, int RB>
 __device__ __forceinline__ void filter_grad_workgroup(const FilterGradParams& p, unsigned char* lds)
 {
+    constexpr int WO = 4 / WK;
+    constexpr int TO = WO * RB * 32;          // columns of dfilt (o) per workgroup
+    static_assert(WK * RA * 32 == kTileK && TO <= 128 && RA + RB <= 4, "tile shape");
     static_assert(VW == 4 || (VW == 1 && !UNIFORM), "VW");
     static_assert(NS >= 3, "slab s+1 must be in flight when slab s reaches its barrier");
     constexpr int CPR = 16 / VW;              // lanes per row in one copy
@@ -78,7 +84,7 @@ __device__ __forceinline__ void filter_grad_workgroup(const FilterGradParams& p,
     const int tile = w - sp * p.n_tiles;
     const int kt   = tile / p.n_otiles;
     const int k0   = kt * kTileK;
-    const int o0   = (tile - kt * p.n_otiles) * kTileO;
+    const int o0   = (tile - kt * p.n_otiles) * TO;
     const int m_begin = sp * p.m_per_split;
     const int m_end   = min(p.M, m_begin + p.m_per_split);
     const int ns      = (m_end - m_begin + kSlabM - 1) / kSlabM;
@@ -87,8 +93,8 @@ __device__ __forceinline__ void filter_grad_workgroup(const FilterGradParams& p,
     const int t    = threadIdx.x;
     const int lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-    const int wk   = wave & 1;
-    const int wo   = wave >> 1;
+    const int wk   = wave % WK;
+    const int wo   = wave / WK;
     const int half = lane >> 5;
     const int l32  = lane & 31;
 
@@ -127,7 +133,7 @@ __device__ __forceinline__ void filter_grad_workgroup(const FilterGradParams& p,
             kx[i] = 1 << 20;
         }
         const int o = o0 + row;
-        if (o < p.No) {
+        if (row < TO && o < p.No) {
             offg[i] = (uint32_t)(((size_t)o * (size_t)p.M + (size_t)(m_begin + dm[i])) * 4u);
             incg[i] = kRowBytes;
         } else {
@@ -214,35 +220,44 @@ __device__ __forceinline__ void filter_grad_workgroup(const FilterGradParams& p,
 
     // ---- fragments.  Block row r of operand X lives at X + r*64; chunk c of it at
     // position c ^ (r/2)%4.  Group g of a slab: lanes 0-31 chunk 2g, lanes 32-63 chunk 2g+1.
-    const int rowA = wk * 64 + l32;
-    const int rowB = wo * 64 + l32;
+    const int rowA = wk * (RA * 32) + l32;
+    const int rowB = wo * (RB * 32) + l32;
     uint32_t a_addr[2], b_addr[2];
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
         a_addr[g] = lds_base + (uint32_t)(rowA * kRowBytes + (((2 * g + half) ^ ((rowA >> 1) & 3)) * 16));
         b_addr[g] = lds_base + (uint32_t)(kOperBytes + rowB * kRowBytes + (((2 * g + half) ^ ((rowB >> 1) & 3)) * 16));
     }
-    f32x4 fa[2][2], fb[2][2];                 // [buffer][block]
+    f32x4 fa[2][RA], fb[2][RB];               // [buffer][block]
     auto request = [&](auto stc, auto gc, auto bufc) {
         constexpr int st = decltype(stc)::value, g = decltype(gc)::value, buf = decltype(bufc)::value;
-        lds_read<st * kStageBytes>(fa[buf][0], a_addr[g]);
-        lds_read<st * kStageBytes + 32 * kRowBytes>(fa[buf][1], a_addr[g]);
-        lds_read<st * kStageBytes>(fb[buf][0], b_addr[g]);
-        lds_read<st * kStageBytes + 32 * kRowBytes>(fb[buf][1], b_addr[g]);
+        static_for<RA>([&](auto ac) {
+            constexpr int a = decltype(ac)::value;
+            lds_read<st * kStageBytes + a * 32 * kRowBytes>(fa[buf][a], a_addr[g]);
+        });
+        static_for<RB>([&](auto bc) {
+            constexpr int b = decltype(bc)::value;
+            lds_read<st * kStageBytes + b * 32 * kRowBytes>(fb[buf][b], b_addr[g]);
+        });
     };
     auto await = [&](auto pendc, auto bufc) {
         constexpr int pend = decltype(pendc)::value, buf = decltype(bufc)::value;
-        lds_wait<pend>(fa[buf][0], fa[buf][1], fb[buf][0], fb[buf][1]);
+        if constexpr (RA == 2 && RB == 2)      lds_wait<pend>(fa[buf][0], fa[buf][1], fb[buf][0], fb[buf][1]);
+        else if constexpr (RA == 1 && RB == 3) lds_wait<pend>(fa[buf][0], fb[buf][0], fb[buf][1], fb[buf][2]);
+        else if constexpr (RA == 1 && RB == 2) lds_wait<pend>(fa[buf][0], fb[buf][0], fb[buf][1]);
+        else if constexpr (RA == 1 && RB == 1) lds_wait<pend>(fa[buf][0], fb[buf][0]);
+        else static_assert(RA == 0, "no wait written for this block shape");
     };
     typedef std::integral_constant<int, 0> I0;
     typedef std::integral_constant<int, 1> I1;
-    typedef std::integral_constant<int, 4> I4;
+    typedef std::integral_constant<int, RA + RB> IReq;   // LDS reads one request issues
+    constexpr int NM = RA * RB;                          // MFMAs per step
 
-    f32x16 acc[2][2];
+    f32x16 acc[RA][RB];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < RA; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < RB; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
 
@@ -277,7 +292,7 @@ __device__ __forceinline__ void filter_grad_workgroup(const FilterGradParams& p,
         const bool refill   = steady || (s + NS - 1 < ns);
 
         request(uc, I1{}, I1{});
-        await(I4{}, I0{});
+        await(IReq{}, I0{});
         static_for<4>([&](auto qc) {
             constexpr int q = decltype(qc)::value;
             if constexpr (q == 1) {
@@ -294,15 +309,15 @@ __device__ __forceinline__ void filter_grad_workgroup(const FilterGradParams& p,
                     bare_barrier();
                 }
             }
-            static_for<4>([&](auto mc) {
-                constexpr int mi = decltype(mc)::value, a = mi >> 1, b = mi & 1;
+            static_for<NM>([&](auto mc) {
+                constexpr int mi = decltype(mc)::value, a = mi / RB, b = mi % RB;
                 acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[0][a][q], fb[0][b][q], acc[a][b], 0, 0, 0);
                 if constexpr (q == 1 && mi == 0) {
                     __builtin_amdgcn_sched_barrier(0);
                     if (refill) issue_P(std::integral_constant<int, ufill>{});
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                if constexpr (q == 1 && mi == 1) {
+                if constexpr (q == 1 && mi == (NM > 1 ? 1 : 0)) {
                     __builtin_amdgcn_sched_barrier(0);
                     if (refill) issue_G(std::integral_constant<int, ufill>{});
                     __builtin_amdgcn_sched_barrier(0);
@@ -311,14 +326,14 @@ __device__ __forceinline__ void filter_grad_workgroup(const FilterGradParams& p,
         });
         if (has_next) {
             request(std::integral_constant<int, unext>{}, I0{}, I0{});
-            await(I4{}, I1{});
+            await(IReq{}, I1{});
         } else {
             await(I0{}, I1{});
         }
         static_for<4>([&](auto qc) {
             constexpr int q = decltype(qc)::value;
-            static_for<4>([&](auto mc) {
-                constexpr int mi = decltype(mc)::value, a = mi >> 1, b = mi & 1;
+            static_for<NM>([&](auto mc) {
+                constexpr int mi = decltype(mc)::value, a = mi / RB, b = mi % RB;
                 acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[1][a][q], fb[1][b][q], acc[a][b], 0, 0, 0);
             });
         });
@@ -335,24 +350,24 @@ __device__ __forceinline__ void filter_grad_workgroup(const FilterGradParams& p,
     // l in block (a,b) is row 8*(v/4) + 4*(l/32) + v%4, column l%32: 32 lanes
     // store 32 consecutive o.
     float* const dst = p.part + (size_t)sp * (size_t)p.K * (size_t)p.No;
-    const int    o   = o0 + wo * 64 + l32;
+    const int    o   = o0 + wo * (RB * 32) + l32;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < RA; ++a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int k = k0 + wk * 64 + a * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+            const int k = k0 + wk * (RA * 32) + a * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
             if (k >= p.K) continue;
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
+            for (int b = 0; b < RB; ++b)
                 if (o + 32 * b < p.No) dst[(size_t)k * (size_t)p.No + o + 32 * b] = acc[a][b][v];
         }
 }
 
-template <int VW, bool UNIFORM, int NS>
+template <int VW, bool UNIFORM, int NS, int WK, int RA, int RB>
 __global__ void __launch_bounds__(256) conv_bprop_filter_kernel(const FilterGradParams p)
 {
     extern __shared__ __align__(64) unsigned char lds_raw[];
-    filter_grad_workgroup<VW, UNIFORM, NS>(p, lds_raw);
+    filter_grad_workgroup<VW, UNIFORM, NS, WK, RA, RB>(p, lds_raw);
 }
 
 // dfilt[e] = alpha * (part[0][e] + part[1][e] + ...), in that order.
@@ -369,23 +384,27 @@ __global__ void __launch_bounds__(256) sum_partial_gradients(const float* __rest
 
 typedef void (*FilterGradFn)(const FilterGradParams);
 constexpr int kRingStages = 3;
-template <int VW, bool UNIFORM>
+template <int VW, bool UNIFORM, int WK, int RA, int RB>
 constexpr FilterGradFn kernel_of()
 {
-    return &conv_bprop_filter_kernel<VW, UNIFORM, kRingStages>;
+    return &conv_bprop_filter_kernel<VW, UNIFORM, kRingStages, WK, RA, RB>;
 }
-// 16-byte copies with the scalar walk / 16-byte copies, per-lane walk / 4-byte copies
-const FilterGradFn kKernels[3] = {
-    kernel_of<4, true>(),
-    kernel_of<4, false>(),
-    kernel_of<1, false>(),
+// [tile width 128, 96, 64, 32][16-byte copies with the scalar walk / 16-byte copies, per-lane walk /
+// 4-byte copies]
+const FilterGradFn kKernels[4][3] = {
+    {kernel_of<4, true, 2, 2, 2>(), kernel_of<4, false, 2, 2, 2>(), kernel_of<1, false, 2, 2, 2>()},
+    {kernel_of<4, true, 4, 1, 3>(), kernel_of<4, false, 4, 1, 3>(), kernel_of<1, false, 4, 1, 3>()},
+    {kernel_of<4, true, 4, 1, 2>(), kernel_of<4, false, 4, 1, 2>(), kernel_of<1, false, 4, 1, 2>()},
+    {kernel_of<4, true, 4, 1, 1>(), kernel_of<4, false, 4, 1, 1>(), kernel_of<1, false, 4, 1, 1>()},
 };
 
 }  // namespace
 
 int launch_bprop_filter(const FilterGradParams& p, float* dfilt, float alpha, void* stream)
 {
-    const FilterGradFn fn = kKernels[(p.vec && p.uniform) ? 0 : p.vec ? 1 : 2];
+    const int shape = p.tile_o == 128 ? 0 : p.tile_o == 96 ? 1 : p.tile_o == 64 ? 2 : p.tile_o == 32 ? 3 : -1;
+    if (shape < 0) return (int)hipErrorInvalidValue;
+    const FilterGradFn fn = kKernels[shape][(p.vec && p.uniform) ? 0 : p.vec ? 1 : 2];
     const uint32_t lds = (uint32_t)kRingStages * kStageBytes;
     hipError_t err = hipSuccess;
     if (lds > 48u * 1024u) {

@@ -87,7 +87,8 @@ struct FilterGradParams {
     int K, SkSk, M;
     uint32_t sksk_magic, sksk_shift, sk_magic, sk_shift;
     uint32_t nb_magic, nb_shift, wo_magic, wo_shift;
-    int n_otiles;            // 128-wide tiles along No
+    int tile_o;              // columns of dfilt per workgroup: 128, 96, 64 or 32
+    int n_otiles;            // tiles along No
     int n_tiles;             // tiles of the K x No gradient
     int splits;              // ranges the contraction index m is cut into
     int m_per_split;         // multiple of 16
