@@ -318,10 +318,8 @@ mdnn_status bprop_plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int strid
     return MDNN_OK;
 }
 
-// Filter gradient: 128 x 128 tiles of the K x No result, the contraction over m = (y,x,n) cut
-// into `splits` ranges so that the launch fills the chip.  Cost of a choice, in slabs of 16 m:
-// rounds of 512 co-resident workgroups (two per compute unit) times a workgroup's slabs plus a
-// fixed start-up/store share.
+// Filter gradient: 128-row tiles of the K x No result, the contraction over m = (y,x,n) cut into
+// `splits` ranges so that the launch fills the chip.
 mdnn_status filter_grad_plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int pad,
                              mdnn::FilterGradParams* f, size_t* workspace_bytes)
 {
@@ -354,16 +352,27 @@ mdnn_status filter_grad_plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int
     if (n_tiles > ((int64_t)1 << 24)) return MDNN_ETOOBIG;
     p.n_tiles = (int)n_tiles;
 
+    // How many ranges: one round of workgroups with r = 1, 2 or 3 of them resident per compute
+    // unit (a second round would double the time; three fit by LDS and registers).  Cost of a
+    // choice in slab times of a lone workgroup: the r co-resident workgroups share the matrix
+    // cores, a fuller compute unit hides a little more latency (measured), and every range adds a
+    // partial gradient for the summing kernel to read at about 3.5 bytes/ns.
     const int64_t slabs = (g.M + 15) / 16;
-    const int64_t kSlots = 512, kFixed = 24, kMinSlabs = 8;
-    int64_t best_s = 1, best_cost = -1;
-    const int64_t s_max = std::min<int64_t>(std::max<int64_t>(1, slabs / kMinSlabs), 4096);
-    for (int64_t s = 1; s <= s_max; ++s) {
+    const int64_t kMinSlabs = 8;
+    const int64_t s_max = std::max<int64_t>(1, slabs / kMinSlabs);
+    const double  rel_eff[3] = {0.975, 0.99, 1.0};
+    const double  n_bytes = (double)g.K * (double)No * 4.0;
+    int64_t best_s = 1;
+    double  best_cost = -1.0;
+    for (int r = 1; r <= 3; ++r) {
+        const int64_t slots = 256 * r;
+        const int64_t s     = std::min<int64_t>(std::max<int64_t>(1, slots / n_tiles), s_max);
         const int64_t per   = (slabs + s - 1) / s;
         const int64_t real  = (slabs + per - 1) / per;             // ranges actually needed
-        const int64_t cost  = ((n_tiles * real + kSlots - 1) / kSlots) * (per + kFixed);
+        const int64_t rounds = (n_tiles * real + slots - 1) / slots;
+        const double  cost  = (double)(rounds * per * r) / rel_eff[r - 1] +
+                              (2.0 + (double)real * n_bytes / 3.5e6) / 0.85;
         if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_s = real; }
-        if (n_tiles * s > 8 * kSlots) break;
     }
     p.m_per_split = (int)(((slabs + best_s - 1) / best_s) * 16);
     p.splits = (int)((g.M + p.m_per_split - 1) / p.m_per_split);
