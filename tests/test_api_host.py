@@ -158,6 +158,35 @@ def test_bprop_data_workspace_and_argument_checks(L):
     assert call_b(w=FAKE + 4) == B.MDNN_EALIGN
 
 
+def test_bprop_filter_workspace_and_argument_checks(L):
+    # the workspace holds a whole number of K x No partial gradients, at least one
+    for dims in [(64, 56, 56, 256, 256, 3, 1, 1), (128, 227, 227, 3, 96, 11, 4, 0), (8, 32, 32, 16, 32, 3, 1, 1),
+                 (1, 5, 5, 2, 3, 5, 1, 0), (7, 10, 11, 3, 37, 3, 2, 1)]:
+        st, n = B.mdnn_conv_bprop_filter_workspace(*dims)
+        Nb, Wi, Hi, Nc, No, Sk, stride, pad = dims
+        one = Nc * Sk * Sk * No * 4
+        assert st == B.MDNN_OK and n >= one and n % one == 0, dims
+        _, wo, ho = B.mdnn_out_dims(Wi, Hi, Sk, stride, pad)
+        ranges = n // one
+        assert ranges <= max(1, (wo * ho * Nb + 15) // 16), dims       # never an empty range
+        # one round of workgroups, at most three per compute unit
+        tiles = -(-(Nc * Sk * Sk) // 128) * min(-(-No // w) for w in (128, 96, 64, 32))
+        assert ranges == 1 or ranges * tiles <= 3 * 256 + tiles, dims
+    # any pad is accepted (the data gradient needs pad <= Sk - 1, this one does not)
+    assert B.mdnn_conv_bprop_filter_workspace(8, 5, 5, 3, 12, 3, 1, 4)[0] == B.MDNN_OK
+    assert B.mdnn_conv_bprop_filter_workspace(8, 2, 2, 2, 4, 3, 1, 0)[0] == B.MDNN_EINVAL   # no output
+    assert B.mdnn_conv_bprop_filter_workspace(1 << 12, 1 << 10, 1 << 10, 1, 4, 3, 1, 0)[0] == B.MDNN_ETOOBIG
+    assert L.mdnn_conv_bprop_filter_workspace(8, 8, 8, 2, 4, 3, 1, 1, None) == B.MDNN_ENULL
+    args = (8, 8, 8, 2, 4, 3, 1, 1)
+    need = B.mdnn_conv_bprop_filter_workspace(*args)[1]
+    call_f = lambda i=FAKE, d=FAKE, o=FAKE, w=FAKE, wb=need, a=1.0: L.mdnn_conv_bprop_filter(i, d, o, w, wb, *args, a, None)
+    assert call_f(i=None) == B.MDNN_ENULL and call_f(d=None) == B.MDNN_ENULL
+    assert call_f(o=None) == B.MDNN_ENULL and call_f(w=None) == B.MDNN_ENULL
+    assert call_f(wb=need - 1) == B.MDNN_EINVAL
+    assert call_f(a=float("inf")) == B.MDNN_EINVAL
+    assert call_f(d=FAKE + 8) == B.MDNN_EALIGN
+
+
 def test_status_strings(L):
     seen = {B.status_string(s) for s in range(6)}
     assert len(seen) == 6 and all(seen)

@@ -26,6 +26,19 @@ def asm(tmp_path_factory):
     return out.read_text()
 
 
+@pytest.fixture(scope="module")
+def asm_filter_grad(tmp_path_factory):
+    from paper_1501_06633_amd import build
+    src = [f for f in build.SOURCES if f.endswith("bprop_filter.hip")][0]
+    out = tmp_path_factory.mktemp("isa") / "bprop_filter.s"
+    flags = [f for f in build.HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
+    cmd = [build.hipcc(), *flags, "-I", os.path.join(ROOT, "include"), "-I", build.CSRC,
+           "-S", "--cuda-device-only", "-o", str(out), src]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert res.returncode == 0, res.stdout[-2000:]
+    return out.read_text()
+
+
 def mnemonics(text):
     ops = set()
     for line in text.splitlines():
@@ -65,3 +78,21 @@ def test_no_spills_and_register_budget(asm):
     # the 128x128 kernels must leave room for three waves per SIMD (512 / 3 = 170 registers)
     main = [v for k, v in vgprs.items() if "Li2ELi2ELi2ELi2E" in k]
     assert main and max(main) <= 168, vgprs
+
+
+def test_filter_gradient_kernels(asm_filter_grad):
+    """The same static checks on the filter-gradient kernels."""
+    text = asm_filter_grad
+    ops = mnemonics(text)
+    assert {o for o in ops if o.startswith(("v_mfma", "v_smfmac"))} == {"v_mfma_f32_32x32x2_f32"}
+    assert re.search(r"buffer_load_dwordx4 .* lds", text) and re.search(r"buffer_load_dword .* lds", text)
+    assert "ds_read_b128" in text
+    assert not {o for o in ops if o.startswith(("v_pk_add_f32", "v_pk_mul_f32", "v_pk_fma_f32"))}
+    assert not {o for o in ops if o.startswith(("s_store", "s_buffer_store", "s_atomic", "s_buffer_atomic",
+                                                "s_dcache_wb", "s_dcache_inv", "s_scratch_store"))}
+    assert not any(int(x) for x in re.findall(r"\.vgpr_spill_count:\s+(\d+)", text))
+    assert not any(int(x) for x in re.findall(r"\.private_segment_fixed_size:\s+(\d+)", text))
+    vgprs = dict(zip(re.findall(r"\.name:\s+(\S+)", text), map(int, re.findall(r"\.vgpr_count:\s+(\d+)", text))))
+    # three workgroups per compute unit are planned for: the 16-byte-copy kernels must fit 512 / 3 registers
+    vec = [v for k, v in vgprs.items() if "conv_bprop_filter_kernelILi4E" in k]
+    assert len(vec) == 8 and max(vec) <= 168, vgprs
