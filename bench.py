@@ -131,6 +131,8 @@ def main():
     ap.add_argument("--bprop-filter", action="store_true",
                     help="also time the filter gradient (BPROP w.r.t. the weights) of the five layers; each call "
                          "is the partial-gradient kernel plus the kernel that sums the partials")
+    ap.add_argument("--bprop-layers", default="tiny,conv1,conv2,conv3,vgg",
+                    help="comma-separated layers for --bprop-data / --bprop-filter (default: all five)")
     ap.add_argument("--sgemm", action="store_true",
                     help="time the 1x1 / stride-1 special case, which is a plain SGEMM (the calibration the "
                          "paper's conclusion leans on), next to the vendor library's fp32 matmul")
@@ -267,7 +269,7 @@ def main():
 
     if args.bprop_data:
         rows = {}
-        for name in W.ORDER:
+        for name in [x for x in W.ORDER if x in args.bprop_layers.split(",")]:
             Lb = W.LAYERS[name]
             st, Wo, Ho = B.mdnn_out_dims(Lb.Wi, Lb.Hi, Lb.Sk, Lb.stride, Lb.pad)
             _, filt = W.make_inputs(Lb)
@@ -301,7 +303,7 @@ def main():
 
     if args.bprop_filter:
         rows = {}
-        for name in W.ORDER:
+        for name in [x for x in W.ORDER if x in args.bprop_layers.split(",")]:
             Lb = W.LAYERS[name]
             st, Wo, Ho = B.mdnn_out_dims(Lb.Wi, Lb.Hi, Lb.Sk, Lb.stride, Lb.pad)
             inp, _ = W.make_inputs(Lb)
