@@ -53,6 +53,9 @@ def _load():
     lib.mdnn_oracle_conv_bprop_filter_points.argtypes = [p, p, p, ctypes.c_int64, p, p,
                                                          i, i, i, i, i, i, i, i, f]
     lib.mdnn_oracle_conv_bprop_filter_points.restype = i
+    lib.mdnn_oracle_conv_bprop_data_points.argtypes = [p, p, p, ctypes.c_int64, p, p,
+                                                       i, i, i, i, i, i, i, i, f]
+    lib.mdnn_oracle_conv_bprop_data_points.restype = i
     lib.mdnn_oracle_conv_fprop_points.argtypes = [p, p, p, ctypes.c_int64, p, p,
                                                   i, i, i, i, i, i, i, i, f]
     lib.mdnn_oracle_conv_fprop_points.restype = i
@@ -186,6 +189,32 @@ def conv_bprop_filter_points(inp, dout, idx, Sk, stride, pad, alpha):
     ab = np.empty(idx.shape[0], dtype=np.float64)
     rc = _load().mdnn_oracle_conv_bprop_filter_points(
         inp.ctypes.data, dout.ctypes.data, idx.ctypes.data, idx.shape[0],
+        vals.ctypes.data, ab.ctypes.data,
+        Nb, Wi, Hi, Nc, No, Sk, stride, pad, float(alpha))
+    if rc:
+        raise ValueError("oracle rejected the arguments (index out of range?)")
+    return vals, ab
+
+
+def conv_bprop_data_points(dout, filt, idx, in_hw, stride, pad, alpha):
+    """The data gradient at the (c,iy,ix,n) rows of ``idx`` only.
+    Returns (values float32[npts], abs_sums float64[npts])."""
+    No, Ho, Wo, Nb = dout.shape
+    Nc, Sk, Sk2, No2 = filt.shape
+    Hi, Wi = in_hw
+    if No2 != No or Sk2 != Sk:
+        raise ValueError("filter shape does not match dout")
+    _check(dout, dout.shape, "dout")
+    _check(filt, filt.shape, "filt")
+    if out_dims(Wi, Hi, Sk, stride, pad) != (Wo, Ho):
+        raise ValueError("dout spatial size does not match the forward geometry")
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    if idx.ndim != 2 or idx.shape[1] != 4:
+        raise ValueError("idx must be (npts, 4)")
+    vals = np.empty(idx.shape[0], dtype=np.float32)
+    ab = np.empty(idx.shape[0], dtype=np.float64)
+    rc = _load().mdnn_oracle_conv_bprop_data_points(
+        dout.ctypes.data, filt.ctypes.data, idx.ctypes.data, idx.shape[0],
         vals.ctypes.data, ab.ctypes.data,
         Nb, Wi, Hi, Nc, No, Sk, stride, pad, float(alpha))
     if rc:

@@ -382,3 +382,47 @@ int mdnn_oracle_conv_bprop_filter_points(const float* in, const float* dout,
     }
     return bad;
 }
+
+/*
+ * The data gradient at selected input elements only: idx holds npts rows
+ * (c, iy, ix, n).  Same definition as mdnn_oracle_conv_bprop_data.
+ * Returns 0, or 1 when an argument or an index is out of range.
+ */
+int mdnn_oracle_conv_bprop_data_points(const float* dout, const float* filt,
+                                       const int* idx, long long npts,
+                                       float* val, double* abs_val,
+                                       int Nb, int Wi, int Hi, int Nc, int No,
+                                       int Sk, int stride, int pad, float alpha)
+{
+    int Wo, Ho;
+    if (!dout || !filt || !idx || !val || npts < 0) return 1;
+    if (Nb < 1 || Nc < 1 || No < 1) return 1;
+    if (mdnn_oracle_out_dims(Wi, Hi, Sk, stride, pad, &Wo, &Ho)) return 1;
+    int bad = 0;
+
+#pragma omp parallel for schedule(dynamic, 16) reduction(|:bad)
+    for (long long i = 0; i < npts; ++i) {
+        int c = idx[4 * i + 0], iy = idx[4 * i + 1], ix = idx[4 * i + 2], n = idx[4 * i + 3];
+        if (c < 0 || c >= Nc || iy < 0 || iy >= Hi || ix < 0 || ix >= Wi || n < 0 || n >= Nb) {
+            bad |= 1;
+            continue;
+        }
+        double S = 0.0, A = 0.0;
+        for (int o = 0; o < No; ++o)
+            for (int ky = 0; ky < Sk; ++ky) {
+                int ty = iy + pad - ky;                     /* = y * stride */
+                if (ty < 0 || ty % stride != 0 || ty / stride >= Ho) continue;
+                for (int kx = 0; kx < Sk; ++kx) {
+                    int tx = ix + pad - kx;
+                    if (tx < 0 || tx % stride != 0 || tx / stride >= Wo) continue;
+                    double p = (double)dout[(((size_t)o * Ho + ty / stride) * Wo + tx / stride) * (size_t)Nb + n] *
+                               (double)filt[(((size_t)c * Sk + ky) * Sk + kx) * (size_t)No + o];
+                    S += p;
+                    A += fabs(p);
+                }
+            }
+        val[i] = (float)((double)alpha * S);
+        if (abs_val) abs_val[i] = A;
+    }
+    return bad;
+}

@@ -88,6 +88,29 @@ def test_strided_first_layer_gradient(env):
     check(got, want, absum, L.alpha, "conv1")
 
 
+@pytest.mark.parametrize("name", sorted(W.TABLE1))
+def test_paper_table1_shapes_sampled(env, name):
+    """The ten layer shapes of the paper's Table 1 at full size (minibatch 128): 20 000 sampled
+    elements of din plus its corners against the oracle's one-by-one evaluation.  The two
+    first layers (stride 4) go through the dilated path."""
+    _, B, oracle = env
+    L, _ = W.TABLE1[name]
+    say(f"[bprop-table1] layer={name} dims={L.dims()}")
+    dout, filt = make_grad(L, oracle)
+    got = run_gpu(env, L, dout, filt)
+    rng = np.random.default_rng(L.seed + 2)
+    npts = 20000
+    idx = np.stack([rng.integers(0, L.Nc, npts), rng.integers(0, L.Hi, npts),
+                    rng.integers(0, L.Wi, npts), rng.integers(0, L.Nb, npts)], axis=1).astype(np.int32)
+    idx[0] = (0, 0, 0, 0)
+    idx[1] = (L.Nc - 1, L.Hi - 1, L.Wi - 1, L.Nb - 1)
+    idx[2] = (L.Nc - 1, 0, L.Wi - 1, 0)
+    idx[3] = (0, L.Hi - 1, 0, L.Nb - 1)
+    vals, absum = oracle.conv_bprop_data_points(dout, filt, idx, (L.Hi, L.Wi), L.stride, L.pad, L.alpha)
+    c, iy, ix, n = idx.T
+    check(got[c, iy, ix, n], vals, absum, L.alpha, name)
+
+
 ODD = [
     # name             Nb  Hi  Wi  Nc  No  Sk st pad alpha
     ("ragged",         12, 11,  9,  5, 36, 3, 1, 1, 0.5),

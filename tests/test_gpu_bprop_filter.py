@@ -91,6 +91,30 @@ def test_layer_gradient_integer_bitwise(env, name):
     np.testing.assert_array_equal(got, want)
 
 
+@pytest.mark.parametrize("name", sorted(W.TABLE1))
+def test_paper_table1_shapes_sampled(env, name):
+    """The ten layer shapes of the paper's Table 1 at full size (minibatch 128): 20 000 sampled
+    elements of dfilt plus its corners against the oracle's one-by-one evaluation.  K reaches
+    9216 and No 1024 here (72 x 8 tiles), so the contraction is not cut at all for the largest."""
+    _, B, oracle = env
+    L, _ = W.TABLE1[name]
+    st, need = B.mdnn_conv_bprop_filter_workspace(L.Nb, L.Wi, L.Hi, L.Nc, L.No, L.Sk, L.stride, L.pad)
+    say(f"[bprop-filter-table1] layer={name} dims={L.dims()} ranges={need // (L.Nc * L.Sk * L.Sk * L.No * 4)}")
+    inp, dout = make_pair(L, oracle)
+    got = run_gpu(env, L, inp, dout)
+    rng = np.random.default_rng(L.seed + 1)
+    npts = 20000
+    idx = np.stack([rng.integers(0, L.Nc, npts), rng.integers(0, L.Sk, npts),
+                    rng.integers(0, L.Sk, npts), rng.integers(0, L.No, npts)], axis=1).astype(np.int32)
+    idx[0] = (0, 0, 0, 0)
+    idx[1] = (L.Nc - 1, L.Sk - 1, L.Sk - 1, L.No - 1)
+    idx[2] = (L.Nc - 1, 0, L.Sk - 1, 0)
+    idx[3] = (0, L.Sk - 1, 0, L.No - 1)
+    vals, absum = oracle.conv_bprop_filter_points(inp, dout, idx, L.Sk, L.stride, L.pad, L.alpha)
+    c, ky, kx, o = idx.T
+    check(got[c, ky, kx, o], vals, absum, L.alpha, name)
+
+
 ODD = [
     # name             Nb  Hi  Wi  Nc  No  Sk st pad alpha
     ("ragged",         12, 11,  9,  5, 36, 3, 1, 1, 0.5),    # Nb % 4 == 0 only: 16-byte copies, per-lane walk

@@ -123,3 +123,19 @@ def test_rejects_mismatched_geometry(oracle_mod):
     with pytest.raises(ValueError):
         oracle_mod.conv_bprop_data(np.zeros((2, 3, 3, 2), np.float32), np.zeros((1, 3, 3, 2), np.float32),
                                    (9, 9), 2, 0, 1.0)
+
+
+def test_points_agree_with_the_full_function(oracle_mod):
+    Nb, Nc, Hi, Wi, No, Sk, stride, pad = 4, 3, 10, 9, 5, 3, 2, 1
+    rng = np.random.default_rng(6)
+    Wo, Ho = oracle_mod.out_dims(Wi, Hi, Sk, stride, pad)
+    dout = rng.uniform(-1, 1, size=(No, Ho, Wo, Nb)).astype(np.float32)
+    filt = rng.uniform(-1, 1, size=(Nc, Sk, Sk, No)).astype(np.float32)
+    full, absum = oracle_mod.conv_bprop_data(dout, filt, (Hi, Wi), stride, pad, 1.5)
+    idx = np.stack([rng.integers(0, Nc, 200), rng.integers(0, Hi, 200), rng.integers(0, Wi, 200),
+                    rng.integers(0, Nb, 200)], axis=1).astype(np.int32)
+    vals, ab = oracle_mod.conv_bprop_data_points(dout, filt, idx, (Hi, Wi), stride, pad, 1.5)
+    np.testing.assert_array_equal(vals, full[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]])
+    np.testing.assert_array_equal(ab, absum[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]])
+    with pytest.raises(ValueError):
+        oracle_mod.conv_bprop_data_points(dout, filt, np.array([[0, Hi, 0, 0]], np.int32), (Hi, Wi), stride, pad, 1.0)
