@@ -267,73 +267,57 @@ def main():
         log(f"[bench] rotating {nsets} buffer sets: {rms:.5f} ms/step, {result['rotating']['tflops']} TFLOP/s")
         del sets
 
-    if args.bprop_data:
-        rows = {}
-        for name in [x for x in W.ORDER if x in args.bprop_layers.split(",")]:
-            Lb = W.LAYERS[name]
-            st, Wo, Ho = B.mdnn_out_dims(Lb.Wi, Lb.Hi, Lb.Sk, Lb.stride, Lb.pad)
-            _, filt = W.make_inputs(Lb)
+    def time_gradient(kind, Lb, steps):
+        """ms per call of one gradient of layer Lb (all kernels of the call), after a timed warm-up."""
+        st, Wo, Ho = B.mdnn_out_dims(Lb.Wi, Lb.Hi, Lb.Sk, Lb.stride, Lb.pad)
+        inp, filt = W.make_inputs(Lb)
+        d_g = torch.randn((Lb.No, Ho, Wo, Lb.Nb), device="cuda")
+        dims = (Lb.Nb, Lb.Wi, Lb.Hi, Lb.Nc, Lb.No, Lb.Sk, Lb.stride, Lb.pad)
+        if kind == "data":
             d_f = torch.from_numpy(filt).cuda()
-            d_g = torch.randn((Lb.No, Ho, Wo, Lb.Nb), device="cuda")
-            din = torch.empty((Lb.Nc, Lb.Hi, Lb.Wi, Lb.Nb), device="cuda")
-            st, need = B.mdnn_conv_bprop_data_workspace(Lb.Nb, Lb.Wi, Lb.Hi, Lb.Nc, Lb.No, Lb.Sk, Lb.stride, Lb.pad)
+            res = torch.empty((Lb.Nc, Lb.Hi, Lb.Wi, Lb.Nb), device="cuda")
+            st, need = B.mdnn_conv_bprop_data_workspace(*dims)
             ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+            call = lambda: B.mdnn_conv_bprop_data(d_g, d_f, (Lb.Hi, Lb.Wi), Lb.stride, Lb.pad, Lb.alpha,
+                                                  din=res, workspace=ws)
+        else:
+            d_in = torch.from_numpy(inp).cuda()
+            res = torch.empty((Lb.Nc, Lb.Sk, Lb.Sk, Lb.No), device="cuda")
+            st, need = B.mdnn_conv_bprop_filter_workspace(*dims)
+            ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+            call = lambda: B.mdnn_conv_bprop_filter(d_in, d_g, Lb.Sk, Lb.stride, Lb.pad, Lb.alpha,
+                                                    dfilt=res, workspace=ws)
 
-            def launch(n):
-                for _ in range(n):
-                    B.mdnn_conv_bprop_data(d_g, d_f, (Lb.Hi, Lb.Wi), Lb.stride, Lb.pad, Lb.alpha, din=din, workspace=ws)
-            launch(5)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(); launch(20); e1.record(); torch.cuda.synchronize()
-            per = e0.elapsed_time(e1) / 20
-            launch(int(WARM_MS_FLOOR / max(per, 1e-3)) + 1)
-            torch.cuda.synchronize()
-            steps = {"tiny": 200, "conv1": 20, "conv2": 50, "conv3": 100, "vgg": 30}[name]
-            e0.record(); launch(steps); e1.record(); torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / steps
-            # required work: every forward multiply-add has one counterpart in the gradient
-            fl = B.mdnn_conv_flops(Lb.Nb, Wo, Ho, Lb.Nc, Lb.No, Lb.Sk)
-            rows[name] = {"ms": round(ms, 5), "tflops": round(fl / ms / 1e9, 3),
-                          "frac_peak": round(fl / ms / 1e9 / PEAK_FP32_MATRIX_TFLOPS, 4),
-                          "stride": Lb.stride, "workspace_bytes": need}
-            log(f"[bench] bprop-data {name:6s} {ms:9.5f} ms {rows[name]['tflops']:8.3f} TFLOP/s "
-                f"({100 * rows[name]['frac_peak']:.1f}% of peak, required FLOPs) stride={Lb.stride}")
-        result["bprop_data"] = rows
+        def launch(n):
+            for _ in range(n):
+                call()
+        launch(5)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); launch(10); e1.record(); torch.cuda.synchronize()
+        per = e0.elapsed_time(e1) / 10
+        launch(int(WARM_MS_FLOOR / max(per, 1e-3)) + 1)
+        torch.cuda.synchronize()
+        e0.record(); launch(steps); e1.record(); torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        # required work: every forward multiply-add has one counterpart in the gradient
+        fl = B.mdnn_conv_flops(Lb.Nb, Wo, Ho, Lb.Nc, Lb.No, Lb.Sk)
+        return {"ms": round(ms, 5), "tflops": round(fl / ms / 1e9, 3),
+                "frac_peak": round(fl / ms / 1e9 / PEAK_FP32_MATRIX_TFLOPS, 4),
+                "stride": Lb.stride, "workspace_bytes": need}
 
-    if args.bprop_filter:
+    for kind, flag in (("data", args.bprop_data), ("filter", args.bprop_filter)):
+        if not flag:
+            continue
         rows = {}
         for name in [x for x in W.ORDER if x in args.bprop_layers.split(",")]:
             Lb = W.LAYERS[name]
-            st, Wo, Ho = B.mdnn_out_dims(Lb.Wi, Lb.Hi, Lb.Sk, Lb.stride, Lb.pad)
-            inp, _ = W.make_inputs(Lb)
-            d_in = torch.from_numpy(inp).cuda()
-            d_g = torch.randn((Lb.No, Ho, Wo, Lb.Nb), device="cuda")
-            dfilt = torch.empty((Lb.Nc, Lb.Sk, Lb.Sk, Lb.No), device="cuda")
-            st, need = B.mdnn_conv_bprop_filter_workspace(Lb.Nb, Lb.Wi, Lb.Hi, Lb.Nc, Lb.No, Lb.Sk, Lb.stride, Lb.pad)
-            ws = torch.empty(need, dtype=torch.uint8, device="cuda")
-
-            def launch(n):
-                for _ in range(n):
-                    B.mdnn_conv_bprop_filter(d_in, d_g, Lb.Sk, Lb.stride, Lb.pad, Lb.alpha, dfilt=dfilt, workspace=ws)
-            launch(5)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(); launch(20); e1.record(); torch.cuda.synchronize()
-            per = e0.elapsed_time(e1) / 20
-            launch(int(WARM_MS_FLOOR / max(per, 1e-3)) + 1)
-            torch.cuda.synchronize()
-            steps = {"tiny": 200, "conv1": 100, "conv2": 50, "conv3": 100, "vgg": 30}[name]
-            e0.record(); launch(steps); e1.record(); torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / steps
-            # required work: every forward multiply-add has one counterpart in the gradient
-            fl = B.mdnn_conv_flops(Lb.Nb, Wo, Ho, Lb.Nc, Lb.No, Lb.Sk)
-            rows[name] = {"ms": round(ms, 5), "tflops": round(fl / ms / 1e9, 3),
-                          "frac_peak": round(fl / ms / 1e9 / PEAK_FP32_MATRIX_TFLOPS, 4),
-                          "workspace_bytes": need}
-            log(f"[bench] bprop-filter {name:6s} {ms:9.5f} ms {rows[name]['tflops']:8.3f} TFLOP/s "
-                f"({100 * rows[name]['frac_peak']:.1f}% of peak, required FLOPs) workspace {need / 1e6:.1f} MB")
-        result["bprop_filter"] = rows
+            steps = {"tiny": 200, "conv1": 20 if kind == "data" else 100, "conv2": 50, "conv3": 100, "vgg": 30}[name]
+            rows[name] = time_gradient(kind, Lb, steps)
+            log(f"[bench] bprop-{kind} {name:6s} {rows[name]['ms']:9.5f} ms {rows[name]['tflops']:8.3f} TFLOP/s "
+                f"({100 * rows[name]['frac_peak']:.1f}% of peak, required FLOPs) stride={Lb.stride} "
+                f"workspace {rows[name]['workspace_bytes'] / 1e6:.1f} MB")
+        result["bprop_" + kind] = rows
 
     if args.sgemm:
         # out (No x M) = filt^T (No x K) . in (K x M) with M = Hi*Wi*Nb: a 1x1 convolution
@@ -379,6 +363,12 @@ def main():
                           "frac_peak": r["frac_peak"], "paper_gtx980_efficiency": paper_ce / 100.0}
             log(f"[bench] table1 {name:18s} {r['ms']:8.4f} ms {r['tflops']:7.2f} TFLOP/s "
                 f"{100 * r['frac_peak']:5.1f}% of peak   (paper, GTX 980: {paper_ce}%)  variant={r['variant']}")
+            for kind, flag in (("data", args.bprop_data), ("filter", args.bprop_filter)):
+                if flag:
+                    g = time_gradient(kind, L1, 5 if (kind == "data" and L1.stride > 1) else 40)
+                    rows[name]["bprop_" + kind] = g
+                    log(f"[bench] table1 {name:18s} bprop-{kind}: {g['ms']:8.4f} ms {g['tflops']:7.2f} TFLOP/s "
+                        f"{100 * g['frac_peak']:5.1f}% of peak")
         result["table1"] = rows
 
     if not args.no_cpu_baseline:

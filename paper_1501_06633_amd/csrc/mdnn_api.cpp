@@ -352,27 +352,34 @@ mdnn_status filter_grad_plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int
     if (n_tiles > ((int64_t)1 << 24)) return MDNN_ETOOBIG;
     p.n_tiles = (int)n_tiles;
 
-    // How many ranges: one round of workgroups with r = 1, 2 or 3 of them resident per compute
-    // unit (a second round would double the time; three fit by LDS and registers).  Cost of a
-    // choice in slab times of a lone workgroup: the r co-resident workgroups share the matrix
-    // cores, a fuller compute unit hides a little more latency (measured), and every range adds a
-    // partial gradient for the summing kernel to read at about 3.5 bytes/ns.
+    // How many ranges.  Workgroups are dealt evenly to the 256 compute units and a unit works
+    // through its share at the matrix rate however many of them are resident at once (up to three
+    // fit by LDS and registers), so a choice costs
+    //     ceil(tiles * ranges / 256) * slabs per range,
+    // a little more when fewer than three are resident (less latency hidden; measured), plus the
+    // summing kernel's reads of one partial gradient per range at about 3.5 bytes/ns.  Measured on
+    // the 5x5 layer with 38 tiles: 13 ranges (494 workgroups) 88 %, 14 (532) 64 %, 20 (760) 90 %,
+    // 27 (1026) 73 %, 40 (1520) 88 %, as this model predicts.
     const int64_t slabs = (g.M + 15) / 16;
     const int64_t kMinSlabs = 8;
     const int64_t s_max = std::max<int64_t>(1, slabs / kMinSlabs);
+    const int64_t s_cap = std::min<int64_t>(s_max, std::max<int64_t>(1, (12 * 256) / n_tiles + 1));
     const double  rel_eff[3] = {0.975, 0.99, 1.0};
     const double  n_bytes = (double)g.K * (double)No * 4.0;
+    const double  slab_us = 0.85 * (double)p.tile_o / 128.0;
+    const bool    small_gradient = g.K * (int64_t)No < ((int64_t)1 << 18);
     int64_t best_s = 1;
     double  best_cost = -1.0;
-    for (int r = 1; r <= 3; ++r) {
-        const int64_t slots = 256 * r;
-        const int64_t s     = std::min<int64_t>(std::max<int64_t>(1, slots / n_tiles), s_max);
-        const int64_t per   = (slabs + s - 1) / s;
-        const int64_t real  = (slabs + per - 1) / per;             // ranges actually needed
-        const int64_t rounds = (n_tiles * real + slots - 1) / slots;
-        const double  cost  = (double)(rounds * per * r) / rel_eff[r - 1] +
-                              (2.0 + (double)real * n_bytes / 3.5e6) / 0.85;
-        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_s = real; }
+    for (int64_t s = 1; s <= s_cap; ++s) {
+        const int64_t per    = (slabs + s - 1) / s;
+        const int64_t real   = (slabs + per - 1) / per;            // ranges actually needed
+        const int64_t per_cu = (n_tiles * real + 255) / 256;       // workgroups on the busiest unit
+        // in microseconds: a slab of a lone 128-wide workgroup takes 0.85, narrower ones in proportion;
+        // the summing kernel for small gradients walks the ranges in chains (latency, not bytes)
+        const double  main_us = (double)(per_cu * per) * slab_us / rel_eff[std::min<int64_t>(per_cu, 3) - 1];
+        const double  sum_us  = 2.0 + (double)real * n_bytes / 3.5e6 + (small_gradient ? 0.02 * (double)real : 0.0);
+        const double  cost    = main_us + sum_us;
+        if (best_cost < 0 || cost < best_cost - 1e-9) { best_cost = cost; best_s = real; }
     }
     p.m_per_split = (int)(((slabs + best_s - 1) / best_s) * 16);
     p.splits = (int)((g.M + p.m_per_split - 1) / p.m_per_split);
