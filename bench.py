@@ -127,7 +127,7 @@ def main():
     ap.add_argument("--bprop-data", action="store_true",
                     help="also time the data gradient (BPROP w.r.t. the input, computed by the FPROP kernels on "
                          "the turned-over filter bank) of the five layers; each call includes the filter "
-                         "rearrangement and, for stride > 1, the dilation of the output gradient")
+                         "rearrangement and, for stride > 1, the gather of the residue classes")
     ap.add_argument("--bprop-filter", action="store_true",
                     help="also time the filter gradient (BPROP w.r.t. the weights) of the five layers; each call "
                          "is the partial-gradient kernel plus the kernel that sums the partials")

@@ -98,8 +98,8 @@ const char* mdnn_choose_variant(int Nb, int Wi, int Hi, int Nc, int No,
  * Data gradient (BPROP with respect to the input).  The paper builds FPROP only
  * and states the belief that the same techniques carry over (abstract, Section
  * 3.5); here they do, literally: the gradient is computed by the FPROP kernels
- * as a stride-1 convolution of the (zero-dilated) output gradient with the
- * turned-over, channel/filter-swapped filter bank.
+ * as a stride-1 convolution of the output gradient with the turned-over,
+ * channel/filter-swapped filter bank.
  *
  *   dout  device, fp32, [No][Ho][Wo][Nb]   gradient w.r.t. the forward output
  *   filt  device, fp32, [Nc][Sk][Sk][No]   the forward filter bank, unchanged
@@ -112,11 +112,12 @@ const char* mdnn_choose_variant(int Nb, int Wi, int Hi, int Nc, int No,
  * The dimension arguments are those of the FORWARD call.  pad <= Sk - 1 is
  * required.  `workspace` is device memory of at least the size
  * mdnn_conv_bprop_data_workspace() reports (16-byte aligned); it receives the
- * rearranged filter bank and, for stride > 1, the dilated gradient, and may be
- * reused or freed once the stream has passed this call.  For stride > 1 the
- * result is correct but the matrix cores also multiply the inserted zeros
- * (stride^2 times the necessary work).  Same stream, ownership and error rules
- * as mdnn_conv_fprop.
+ * rearranged filter bank and, for stride > 1, the per-residue-class results
+ * that a last kernel interleaves into din (input pixels are split by
+ * (iy + pad, ix + pad) modulo the stride; every class is a stride-1 problem with
+ * a ceil(Sk/stride)^2 sub-filter, and all classes run as one convolution).  It
+ * may be reused or freed once the stream has passed this call.  Same stream,
+ * ownership and error rules as mdnn_conv_fprop.
  */
 mdnn_status mdnn_conv_bprop_data_workspace(int Nb, int Wi, int Hi, int Nc, int No,
                                            int Sk, int stride, int pad, size_t* bytes);

@@ -10,10 +10,13 @@
 //     din[c][iy][ix][n] = alpha * sum_{o,ky',kx'} D[o][iy-(Sk-1-pad)+ky'][ix-(Sk-1-pad)+kx'][n] * F'[o][ky'][kx'][c],
 //     D[o][stride*y][stride*x][n] = dout[o][y][x][n], zero elsewhere.
 // So the implicit-GEMM kernel, its offset table and its zero-apron handling are
-// reused unchanged; this file only holds the two small layout kernels that
-// prepare F' and D in the caller's workspace.  For stride 1, D is dout itself.
-// For stride s > 1 the matrix cores also multiply the inserted zeros (s*s times
-// the necessary work): correct, not yet efficient.
+// reused unchanged; this file only holds the small layout kernels around it.
+// Stride 1: one transpose of the filter bank into the caller's workspace.
+// Stride s > 1: dilating dout would make the matrix cores multiply s*s - 1
+// inserted zeros per value; instead the input pixels are split by the residue
+// class of (iy + pad, ix + pad) modulo s, every class is a stride-1 correlation
+// of dout with its own ceil(Sk/s)^2 sub-filter, all classes run as one forward
+// convolution with s*s*Nc filters, and a gather interleaves the classes into din.
 #include <hip/hip_runtime.h>
 
 #include "mdnn_internal.h"
@@ -45,26 +48,58 @@ __global__ void __launch_bounds__(256) flip_transpose_filters(const float* __res
     }
 }
 
-// D[o][ty][tx][n] = dout[o][ty/s][tx/s][n] where both are multiples of s and inside, else 0.
-__global__ void __launch_bounds__(256) dilate_gradient(const float* __restrict__ dout,
-                                                       float* __restrict__ d,
-                                                       int No, int Ho, int Wo, int Hd, int Wd, int Nb, int stride)
+// Stride s > 1.  An input row iy only meets the taps ky = ry + s*t with ry = (iy + pad) % s, and
+// then the output rows y = (iy + pad)/s - t: per residue class (ry, rx) the gradient is a
+// stride-1 correlation of dout with a T x T sub-filter, T = ceil(Sk/s).  All s*s classes read the
+// same dout with the same geometry, so they run as ONE forward convolution with s*s*Nc "filters":
+// row k' = (o*T + ty')*T + tx', column cls*Nc + c of the bank built here holds
+// filt[c][ry + s*(T-1-ty')][rx + s*(T-1-tx')][o], or 0 where that tap does not exist.
+__global__ void __launch_bounds__(256) class_filters(const float* __restrict__ filt, float* __restrict__ fc,
+                                                     int Nc, int No, int Sk, int stride, int T)
 {
-    const size_t total = (size_t)No * Hd * Wd * Nb;
+    const int    cols  = stride * stride * Nc;
+    const size_t total = (size_t)No * T * T * cols;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
          i += (size_t)gridDim.x * blockDim.x) {
-        const int    n   = (int)(i % Nb);
-        const size_t pix = i / Nb;
-        const int    tx  = (int)(pix % Wd);
-        const size_t r   = pix / Wd;
-        const int    ty  = (int)(r % Hd);
-        const int    o   = (int)(r / Hd);
-        float v = 0.0f;
-        if (ty % stride == 0 && tx % stride == 0) {
-            const int y = ty / stride, x = tx / stride;
-            if (y < Ho && x < Wo) v = dout[(((size_t)o * Ho + y) * Wo + x) * Nb + n];
+        const int    col = (int)(i % cols);
+        const size_t k   = i / cols;
+        const int    cls = col / Nc, c = col - cls * Nc;
+        const int    ry  = cls / stride, rx = cls - ry * stride;
+        const int    o   = (int)(k / (T * T));
+        const int    r   = (int)(k - (size_t)o * T * T);
+        const int    ty  = r / T, tx = r - ty * T;
+        const int    ky  = ry + stride * (T - 1 - ty);
+        const int    kx  = rx + stride * (T - 1 - tx);
+        fc[i] = (ky < Sk && kx < Sk) ? filt[(((size_t)c * Sk + ky) * Sk + kx) * No + o] : 0.0f;
+    }
+}
+
+// din[c][iy][ix][n] = E[cls*Nc + c][(iy+pad)/s][(ix+pad)/s][n], cls = ((iy+pad)%s)*s + (ix+pad)%s;
+// 0 for pixels beyond the last window (their quotient lies outside E).  E is [s*s*Nc][He][We][Nb].
+template <int VW>
+__global__ void __launch_bounds__(256) gather_classes(const float* __restrict__ e, float* __restrict__ din,
+                                                      int Nc, int Hi, int Wi, int Nb, int He, int We,
+                                                      int stride, int pad)
+{
+    typedef float vec __attribute__((ext_vector_type(VW)));
+    const int    nbv   = Nb / VW;
+    const size_t total = (size_t)Nc * Hi * Wi * nbv;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (size_t)gridDim.x * blockDim.x) {
+        const int    n   = (int)(i % nbv);
+        const size_t pix = i / nbv;
+        const int    ix  = (int)(pix % Wi);
+        const size_t r   = pix / Wi;
+        const int    iy  = (int)(r % Hi);
+        const int    c   = (int)(r / Hi);
+        const int    qy  = (iy + pad) / stride, ry = (iy + pad) - qy * stride;
+        const int    qx  = (ix + pad) / stride, rx = (ix + pad) - qx * stride;
+        vec v = 0.0f;
+        if (qy < He && qx < We) {
+            const size_t row = (size_t)(ry * stride + rx) * Nc + c;
+            v = reinterpret_cast<const vec*>(e)[((row * He + qy) * We + qx) * nbv + n];
         }
-        d[i] = v;
+        reinterpret_cast<vec*>(din)[i] = v;
     }
 }
 
@@ -78,14 +113,29 @@ int launch_flip_transpose(const float* filt, float* ft, int Nc, int No, int SkSk
     return (int)hipGetLastError();
 }
 
-int launch_dilate(const float* dout, float* d, int No, int Ho, int Wo, int Hd, int Wd, int Nb, int stride,
-                  void* stream)
+int launch_class_filters(const float* filt, float* fc, int Nc, int No, int Sk, int stride, int T, void* stream)
 {
-    const size_t total = (size_t)No * Hd * Wd * Nb;
+    const size_t total = (size_t)No * T * T * stride * stride * Nc;
     size_t blocks = (total + 255) / 256;
     if (blocks > 256u * 64u) blocks = 256u * 64u;          // grid-stride beyond that
-    hipLaunchKernelGGL(dilate_gradient, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       dout, d, No, Ho, Wo, Hd, Wd, Nb, stride);
+    hipLaunchKernelGGL(class_filters, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       filt, fc, Nc, No, Sk, stride, T);
+    return (int)hipGetLastError();
+}
+
+int launch_gather_classes(const float* e, float* din, int Nc, int Hi, int Wi, int Nb, int He, int We,
+                          int stride, int pad, void* stream)
+{
+    const int    vw    = (Nb % 4 == 0) ? 4 : 1;
+    const size_t total = (size_t)Nc * Hi * Wi * (Nb / vw);
+    size_t blocks = (total + 255) / 256;
+    if (blocks > 256u * 64u) blocks = 256u * 64u;
+    if (vw == 4)
+        hipLaunchKernelGGL(gather_classes<4>, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                           e, din, Nc, Hi, Wi, Nb, He, We, stride, pad);
+    else
+        hipLaunchKernelGGL(gather_classes<1>, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                           e, din, Nc, Hi, Wi, Nb, He, We, stride, pad);
     return (int)hipGetLastError();
 }
 

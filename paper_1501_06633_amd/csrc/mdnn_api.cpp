@@ -290,11 +290,16 @@ mdnn_status mdnn_conv_fprop(const float* in, const float* filt, float* out,
 namespace {
 
 // Geometry of the forward convolution whose stride-1 run yields the data gradient.
+// stride 1: the turned-over bank (K' = No*Sk*Sk rows, Nc columns), pad Sk-1-pad, written to din.
+// stride s: T = ceil(Sk/s); the residue-class bank (No*T*T rows, s*s*Nc columns), pad T-1, written
+//           to E [s*s*Nc][Ho+T-1][Wo+T-1][Nb] in the workspace, then gathered into din.
 struct BpropPlan {
-    int       Hd, Wd;          // extent of the (dilated) output gradient the kernel reads
-    int       pad_t;           // Sk - 1 - pad
-    size_t    ft_bytes;        // flipped / transposed filter bank
-    size_t    d_offset;        // byte offset of the dilated gradient in the workspace (stride > 1)
+    int       T;               // taps per side of the transposed problem (Sk for stride 1)
+    int       filters_t;       // its filter count (Nc, or s*s*Nc)
+    int       pad_t;           // its pad
+    int       He, We;          // its output extent (Hi x Wi for stride 1)
+    size_t    bank_bytes;      // rearranged filter bank
+    size_t    e_offset;        // byte offset of E in the workspace (stride > 1)
     size_t    total_bytes;
 };
 
@@ -304,17 +309,25 @@ mdnn_status bprop_plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int strid
     const mdnn_status gs = check_geometry(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &g);
     if (gs != MDNN_OK) return gs;
     if (pad > Sk - 1) return MDNN_EINVAL;      // would need a negative pad in the transposed problem
-    b->Hd = Hi + 2 * pad - Sk + 1;             // >= (Ho-1)*stride + 1; the surplus rows are zeros
-    b->Wd = Wi + 2 * pad - Sk + 1;
-    b->pad_t = Sk - 1 - pad;
-    b->ft_bytes = (size_t)g.filt_bytes;
-    b->d_offset = (b->ft_bytes + 255) & ~(size_t)255;
-    b->total_bytes = b->d_offset;
-    if (stride > 1) {
-        const int64_t d_bytes = 4 * (int64_t)No * b->Hd * b->Wd * Nb;
-        if (d_bytes >= kFourGiB) return MDNN_ETOOBIG;
-        b->total_bytes += (size_t)d_bytes;
+    if (stride == 1) {
+        b->T = Sk;  b->filters_t = Nc;  b->pad_t = Sk - 1 - pad;
+        b->He = Hi;  b->We = Wi;
+        b->bank_bytes = (size_t)g.filt_bytes;
+        b->e_offset = (b->bank_bytes + 255) & ~(size_t)255;
+        b->total_bytes = b->e_offset;
+        return MDNN_OK;
     }
+    const int T = (Sk + stride - 1) / stride;
+    const int64_t filters_t = (int64_t)stride * stride * Nc;
+    if (filters_t >= ((int64_t)1 << 24)) return MDNN_ETOOBIG;
+    b->T = T;  b->filters_t = (int)filters_t;  b->pad_t = T - 1;
+    b->He = g.Ho + T - 1;  b->We = g.Wo + T - 1;
+    const int64_t bank_bytes = 4 * (int64_t)No * T * T * filters_t;
+    const int64_t e_bytes = 4 * filters_t * b->He * b->We * Nb;
+    if (bank_bytes >= kFourGiB / 2 || e_bytes >= kFourGiB) return MDNN_ETOOBIG;
+    b->bank_bytes = (size_t)bank_bytes;
+    b->e_offset = (b->bank_bytes + 255) & ~(size_t)255;
+    b->total_bytes = b->e_offset + (size_t)e_bytes;
     return MDNN_OK;
 }
 
@@ -446,25 +459,28 @@ mdnn_status mdnn_conv_bprop_data(const float* dout, const float* filt, float* di
 
     Geometry g;
     check_geometry(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &g);       // succeeded inside bprop_plan
-    float* ft = static_cast<float*>(workspace);
-    float* d  = reinterpret_cast<float*>(static_cast<char*>(workspace) + b.d_offset);
+    float* bank = static_cast<float*>(workspace);
+    float* e    = reinterpret_cast<float*>(static_cast<char*>(workspace) + b.e_offset);
 
-    // the transposed problem: No input channels, Nc filters, stride 1, pad Sk-1-pad, image Hd x Wd
+    // the transposed problem: No input channels of Ho x Wo, b.filters_t filters of T x T, stride 1
     mdnn::ConvParams p;
     int v = -1;
-    const mdnn_status ps = plan(Nb, b.Wd, b.Hd, No, Nc, Sk, 1, b.pad_t, nullptr, &p, &v);
+    const mdnn_status ps = plan(Nb, g.Wo, g.Ho, No, b.filters_t, b.T, 1, b.pad_t, nullptr, &p, &v);
     if (ps != MDNN_OK) return ps;
-    if (p.Ho != Hi || p.Wo != Wi) return MDNN_EINVAL;              // cannot happen: (Hd + 2 pad_t - Sk) + 1 == Hi
+    if (p.Ho != b.He || p.Wo != b.We) return MDNN_EINVAL;          // cannot happen: Ho + 2 pad_t - T + 1 == He
 
-    if (mdnn::launch_flip_transpose(filt, ft, Nc, No, Sk * Sk, stream) != 0) return MDNN_ELAUNCH;
-    const float* src = dout;
-    if (stride > 1) {
-        if (mdnn::launch_dilate(dout, d, No, g.Ho, g.Wo, b.Hd, b.Wd, Nb, stride, stream) != 0) return MDNN_ELAUNCH;
-        src = d;
+    if (stride == 1) {
+        if (mdnn::launch_flip_transpose(filt, bank, Nc, No, Sk * Sk, stream) != 0) return MDNN_ELAUNCH;
+        p.in = dout;  p.filt = bank;  p.out = din;
+        p.alpha = alpha;
+        return mdnn::launch_variant(v, p, stream) == 0 ? MDNN_OK : MDNN_ELAUNCH;
     }
-    p.in = src;  p.filt = ft;  p.out = din;
+    if (mdnn::launch_class_filters(filt, bank, Nc, No, Sk, stride, b.T, stream) != 0) return MDNN_ELAUNCH;
+    p.in = dout;  p.filt = bank;  p.out = e;
     p.alpha = alpha;
-    return mdnn::launch_variant(v, p, stream) == 0 ? MDNN_OK : MDNN_ELAUNCH;
+    if (mdnn::launch_variant(v, p, stream) != 0) return MDNN_ELAUNCH;
+    return mdnn::launch_gather_classes(e, din, Nc, Hi, Wi, Nb, b.He, b.We, stride, pad, stream) == 0
+               ? MDNN_OK : MDNN_ELAUNCH;
 }
 
 mdnn_status mdnn_mfma_peak_probe(float* sink, int blocks, int waves_per_block, int iters,

@@ -74,8 +74,9 @@ int launch_mfma_probe(float* sink, int blocks, int waves_per_block, int iters, v
 
 // Layout kernels of the data gradient (bprop_data.hip); return hipSuccess (0) or the HIP error code.
 int launch_flip_transpose(const float* filt, float* ft, int Nc, int No, int SkSk, void* stream);
-int launch_dilate(const float* dout, float* d, int No, int Ho, int Wo, int Hd, int Wd, int Nb, int stride,
-                  void* stream);
+int launch_class_filters(const float* filt, float* fc, int Nc, int No, int Sk, int stride, int T, void* stream);
+int launch_gather_classes(const float* e, float* din, int Nc, int Hi, int Wi, int Nb, int He, int We,
+                          int stride, int pad, void* stream);
 
 // Filter gradient (bprop_filter.hip): everything a workgroup needs.
 struct FilterGradParams {

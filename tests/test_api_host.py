@@ -142,10 +142,11 @@ def test_bprop_data_workspace_and_argument_checks(L):
     # stride 1: only the rearranged filter bank (Nc*Sk*Sk*No floats), rounded up to 256 bytes
     st, n = B.mdnn_conv_bprop_data_workspace(64, 56, 56, 256, 256, 3, 1, 1)
     assert st == B.MDNN_OK and n == 256 * 9 * 256 * 4
-    # stride 4: plus the dilated gradient No x (Hi+2p-Sk+1)^2 x Nb
+    # stride 4, 11x11: 16 residue classes with 3x3 sub-filters -> a bank of (96*9) x (16*3) floats, and
+    # the per-class results [16*3][55+2][55+2][128] that are then gathered into din
     st, n = B.mdnn_conv_bprop_data_workspace(128, 227, 227, 3, 96, 11, 4, 0)
-    ft = 3 * 121 * 96 * 4
-    assert st == B.MDNN_OK and n == ((ft + 255) // 256) * 256 + 96 * 217 * 217 * 128 * 4
+    bank = 96 * 9 * 48 * 4
+    assert st == B.MDNN_OK and n == ((bank + 255) // 256) * 256 + 48 * 57 * 57 * 128 * 4
     assert B.mdnn_conv_bprop_data_workspace(8, 8, 8, 2, 4, 3, 1, 3)[0] == B.MDNN_EINVAL     # pad > Sk - 1
     assert B.mdnn_conv_bprop_data_workspace(8, 2, 2, 2, 4, 3, 1, 0)[0] == B.MDNN_EINVAL     # no output
     assert L.mdnn_conv_bprop_data_workspace(8, 8, 8, 2, 4, 3, 1, 1, None) == B.MDNN_ENULL

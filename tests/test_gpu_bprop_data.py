@@ -78,7 +78,7 @@ def test_layer_gradient_matches_oracle_everywhere(env, name):
 
 
 def test_strided_first_layer_gradient(env):
-    """conv1 (stride 4, 11x11): the gradient goes through the dilated path; whole tensor."""
+    """conv1 (stride 4, 11x11): the gradient goes through the residue-class path; whole tensor."""
     _, B, oracle = env
     L = W.LAYERS["conv1"]
     say(f"[bprop] layer=conv1 dims={L.dims()}")
@@ -92,7 +92,7 @@ def test_strided_first_layer_gradient(env):
 def test_paper_table1_shapes_sampled(env, name):
     """The ten layer shapes of the paper's Table 1 at full size (minibatch 128): 20 000 sampled
     elements of din plus its corners against the oracle's one-by-one evaluation.  The two
-    first layers (stride 4) go through the dilated path."""
+    first layers (stride 4) go through the residue-class path."""
     _, B, oracle = env
     L, _ = W.TABLE1[name]
     say(f"[bprop-table1] layer={name} dims={L.dims()}")
@@ -122,6 +122,12 @@ ODD = [
     ("pad_max",         8,  6,  6,  3, 12, 3, 1, 2, 1.0),    # pad = Sk - 1
     ("one_window",      4,  5,  5,  4,  8, 5, 1, 0, 1.0),
     ("many_tiles",     32, 15, 13, 20, 200, 3, 1, 1, 1.0),
+    ("s2_5x5_pad2",    16, 13, 11,  6, 20, 5, 2, 2, 1.0),    # T = 3, classes with 9 / 6 / 4 real taps
+    ("s2_4x4",          8, 10, 12,  5, 16, 4, 2, 1, 0.5),    # T = 2, every class full
+    ("s3_7x7_pad3",     8, 17, 15,  4, 12, 7, 3, 3, 1.0),
+    ("s2_odd_batch",    5,  9,  9,  3, 10, 3, 2, 1, 1.0),    # 4-byte gather
+    ("s5_3x3_pad2",     8, 14, 14,  4,  8, 3, 5, 2, 1.0),    # most classes have no tap at all
+    ("s2_one_window",   4,  6,  6,  3,  8, 6, 2, 0, 1.0),
 ]
 
 
