@@ -328,12 +328,11 @@ __device__ __forceinline__ void filter_grad_workgroup(const FilterGradParams& p,
                 }
             });
         });
-        if (has_next) {
-            request(std::integral_constant<int, unext>{}, I0{}, I0{});
-            await(IReq{}, I1{});
-        } else {
-            await(I0{}, I1{});
-        }
+        // always the same request/await pair, also behind the last slab (where it fetches values
+        // nobody uses): a branch here would let the compiler copy a fragment register on one path
+        // before the wait that makes it valid
+        request(std::integral_constant<int, unext>{}, I0{}, I0{});
+        await(IReq{}, I1{});
         static_for<4>([&](auto qc) {
             constexpr int q = decltype(qc)::value;
             static_for<NM>([&](auto mc) {
@@ -349,6 +348,12 @@ __device__ __forceinline__ void filter_grad_workgroup(const FilterGradParams& p,
         static_for<NS>([&](auto uc) {
             if (s0 + decltype(uc)::value < ns) slab(uc, std::false_type{}, s0 + decltype(uc)::value);
         });
+
+    // the fragment request behind the last slab is still in flight: let it land before anything
+    // else may use those registers
+    await(I0{}, I0{});
+    await(I0{}, I1{});
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- partial tile -> workspace [split][K][No].  Accumulator register v of lane
     // l in block (a,b) is row 8*(v/4) + 4*(l/32) + v%4, column l%32: 32 lanes

@@ -287,6 +287,16 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
         else if constexpr (RA == 3) lds_wait<pend>(av[buf][0], av[buf][1], av[buf][2], bv[buf]);
         else lds_wait<pend>(av[buf][0], av[buf][1], av[buf][2], av[buf][3], bv[buf]);
     };
+    auto drain = [&]() {
+        static_for<2>([&](auto bc) {
+            constexpr int buf = decltype(bc)::value;
+            if constexpr (RA == 1) lds_wait<0>(av[buf][0], bv[buf]);
+            else if constexpr (RA == 2) lds_wait<0>(av[buf][0], av[buf][1], bv[buf]);
+            else if constexpr (RA == 3) lds_wait<0>(av[buf][0], av[buf][1], av[buf][2], bv[buf]);
+            else lds_wait<0>(av[buf][0], av[buf][1], av[buf][2], av[buf][3], bv[buf]);
+        });
+        __builtin_amdgcn_sched_barrier(0);
+    };
     typedef std::integral_constant<int, 0> I0;
 
     // table row k: {byte offset of (c,ky,kx) in `in`, tap id}; rows k >= K are {0, 0}
@@ -374,12 +384,11 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
                         request(uc, std::integral_constant<int, j + 1>{}, std::integral_constant<int, cur ^ 1>{});
                         await(std::integral_constant<int, RA + 1>{}, std::integral_constant<int, cur>{});
                     } else {
-                        if (has_next) {
-                            request(std::integral_constant<int, unext>{}, I0{}, std::integral_constant<int, cur ^ 1>{});
-                            await(std::integral_constant<int, RA + 1>{}, std::integral_constant<int, cur>{});
-                        } else {
-                            await(I0{}, std::integral_constant<int, cur>{});
-                        }
+                        // Always the same request/await pair, also behind the last slab (where it
+                        // fetches values nobody uses): a branch here would let the compiler copy
+                        // a fragment register on one path before the wait that makes it valid.
+                        request(std::integral_constant<int, unext>{}, I0{}, std::integral_constant<int, cur ^ 1>{});
+                        await(std::integral_constant<int, RA + 1>{}, std::integral_constant<int, cur>{});
                     }
                     static_for<NM>([&](auto mc) {
                         constexpr int mi = decltype(mc)::value, a = mi / RB, b = mi % RB;
@@ -412,6 +421,9 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
                 static_for<NS>([&](auto uc) {
                     if (s0 + decltype(uc)::value < ns) slab(uc, std::false_type{}, s0 + decltype(uc)::value);
                 });
+            // the fragment request behind the last slab is still in flight: let it land before
+            // anything else may use those registers
+            drain();
         }
     };
     if (interior)          main_loop(std::integral_constant<int, kTapNone>{});

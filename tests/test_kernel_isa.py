@@ -11,6 +11,8 @@ import subprocess
 
 import pytest
 
+import lds_hazard_check
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
@@ -96,3 +98,43 @@ def test_filter_gradient_kernels(asm_filter_grad):
     # three workgroups per compute unit are planned for: the 16-byte-copy kernels must fit 512 / 3 registers
     vec = [v for k, v in vgprs.items() if "conv_bprop_filter_kernelILi4E" in k]
     assert len(vec) == 8 and max(vec) <= 168, vgprs
+
+
+def test_no_register_is_touched_while_an_lds_read_into_it_is_in_flight(asm, asm_filter_grad):
+    """The hand-counted LDS waits hold on every path of every kernel (see lds_hazard_check)."""
+    n, bad = lds_hazard_check.check(asm)
+    assert n >= 11 and not bad, bad[:5]
+    n, bad = lds_hazard_check.check(asm_filter_grad)
+    assert n >= 12 and not bad, bad[:5]
+
+
+_GOOD = """
+k:
+\tds_read_b32 v1, v9
+\tds_read_b32 v2, v9 offset:4
+\ts_waitcnt lgkmcnt(1)
+\tv_add_f32 v3, v1, v1
+\ts_cbranch_scc1 .LBB0_2
+\tds_read_b32 v1, v9 offset:8
+.LBB0_2:
+\ts_waitcnt lgkmcnt(0)
+\tv_add_f32 v3, v2, v1
+\ts_endpgm
+"""
+
+
+def test_the_checker_itself():
+    n, bad = lds_hazard_check.check(_GOOD)
+    assert n == 1 and not bad
+    # a copy before the wait that makes the value valid
+    n, bad = lds_hazard_check.check(_GOOD.replace("\ts_waitcnt lgkmcnt(1)\n", "\tv_mov_b32 v4, v1\n\ts_waitcnt lgkmcnt(1)\n"))
+    assert bad and bad[0][3] == [1]
+    # waiting for too few: the second read is still in flight when v2 is used
+    n, bad = lds_hazard_check.check(_GOOD.replace("lgkmcnt(0)", "lgkmcnt(1)"))
+    assert any(2 in b[3] for b in bad)
+    # only one path is wrong: the read issued on the fall-through path is not waited for
+    n, bad = lds_hazard_check.check(_GOOD.replace(".LBB0_2:\n\ts_waitcnt lgkmcnt(0)", ".LBB0_2:\n\ts_waitcnt lgkmcnt(1)\n\tv_mov_b32 v5, v2"))
+    assert bad and all(b[3] == [1] or b[3] == [2] for b in bad)
+    # reusing the destination register for something else while the read is in flight
+    n, bad = lds_hazard_check.check(_GOOD.replace("\ts_waitcnt lgkmcnt(1)\n", "\tv_mov_b32 v2, 0\n\ts_waitcnt lgkmcnt(1)\n"))
+    assert bad and bad[0][3] == [2]
