@@ -56,7 +56,11 @@ typedef enum mdnn_status {
  * call only enqueues work on `stream` (a hipStream_t; NULL = the default
  * stream) and returns; the result is valid once the stream has been
  * synchronised.  All argument checks happen before anything is enqueued:
- * on any status other than MDNN_OK nothing has been launched.
+ * on any status other than MDNN_OK nothing has been launched.  Nothing is
+ * allocated, cleared with a memset or synchronised, so the call may be recorded
+ * into a HIP graph; the first launch of a kernel on a device also raises that
+ * kernel's LDS limit (a function attribute, not a stream operation), so make
+ * one call outside the capture first.
  */
 mdnn_status mdnn_conv_fprop(const float* in, const float* filt, float* out,
                             int Nb, int Wi, int Hi, int Nc, int No,

@@ -41,6 +41,7 @@
 // addresses as immediates, no scalar tests in the steady state.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <type_traits>
 #include <utility>
 
@@ -646,9 +647,20 @@ int launch_variant(int i, const ConvParams& p, void* stream)
     const uint32_t lds = variant_lds_bytes(i, p.tab_cap);
     hipError_t err = hipSuccess;
     if (lds > 48u * 1024u) {
-        err = hipFuncSetAttribute(reinterpret_cast<const void*>(e.fn),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        // once per kernel, device and size class: a launch should only enqueue (a caller may be
+        // capturing the stream into a graph)
+        static std::atomic<uint64_t> raised[kNumEntries];
+        int dev = 0;
+        err = hipGetDevice(&dev);
         if (err != hipSuccess) return (int)err;
+        const uint64_t bit = 1ull << (dev & 63);
+        if (!(raised[i].load(std::memory_order_acquire) & bit)) {
+            err = hipFuncSetAttribute(reinterpret_cast<const void*>(e.fn),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)variant_lds_bytes(i, kMaxTabEntries));
+            if (err != hipSuccess) return (int)err;
+            raised[i].fetch_or(bit, std::memory_order_release);
+        }
     }
     const dim3 grid((unsigned)(8 * p.tiles_per_xcd + 8 * p.pieces_per_xcd)), block((unsigned)e.info.threads);
     hipLaunchKernelGGL(e.fn, grid, block, lds, static_cast<hipStream_t>(stream), p);

@@ -11,7 +11,7 @@
 namespace {
 
 constexpr int     kComputeUnits = 256;          // MI355X
-constexpr int     kMaxTabEntries = 4096;        // 32 KB of LDS for the offset table
+using mdnn::kMaxTabEntries;
 constexpr int     kStripRows = 8;               // image rows per strip of the 2-D tile order
 constexpr int64_t kFourGiB = (int64_t)1 << 32;
 

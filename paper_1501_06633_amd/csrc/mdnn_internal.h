@@ -8,6 +8,8 @@
 
 namespace mdnn {
 
+constexpr int kMaxTabEntries = 4096;     // offset-table entries resident in LDS at once: 32 KB
+
 // Everything a tile needs, passed by value as the single kernel argument.
 struct ConvParams {
     const float* in;
