@@ -108,6 +108,28 @@ def cpu_baseline(W, name):
             "sample": f"whole layer {name}: all {No_s} output filters, all positions, whole batch, one pass"}
 
 
+def cpu_baseline_gradient(W, name, kind):
+    """The oracle's gradient function on the whole layer, one pass (same role as cpu_baseline)."""
+    import numpy as np
+    import oracle
+
+    L = W.LAYERS[name]
+    inp, filt = W.make_inputs(L)
+    Wo, Ho = oracle.out_dims(L.Wi, L.Hi, L.Sk, L.stride, L.pad)
+    dout = np.random.Generator(np.random.PCG64(L.seed + 99)).standard_normal(
+        size=(L.No, Ho, Wo, L.Nb), dtype=np.float32)
+    flops = oracle.flops(L.Nb, Wo, Ho, L.Nc, L.No, L.Sk)
+    t0 = time.perf_counter()
+    if kind == "data":
+        oracle.conv_bprop_data(dout, filt, (L.Hi, L.Wi), L.stride, L.pad, L.alpha, want_abs=False)
+    else:
+        oracle.conv_bprop_filter(inp, dout, L.Sk, L.stride, L.pad, L.alpha, want_abs=False)
+    dt = time.perf_counter() - t0
+    return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.max_threads(),
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": f"whole layer {name}, {kind} gradient, one pass"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -317,6 +339,13 @@ def main():
             log(f"[bench] bprop-{kind} {name:6s} {rows[name]['ms']:9.5f} ms {rows[name]['tflops']:8.3f} TFLOP/s "
                 f"({100 * rows[name]['frac_peak']:.1f}% of peak, required FLOPs) stride={Lb.stride} "
                 f"workspace {rows[name]['workspace_bytes'] / 1e6:.1f} MB")
+        if not args.no_cpu_baseline and args.workload in rows:
+            log(f"[bench] timing the CPU oracle's {kind} gradient on {args.workload} ...")
+            rows[args.workload]["cpu_baseline"] = cpu_baseline_gradient(W, args.workload, kind)
+            log(f"[bench] oracle: {rows[args.workload]['cpu_baseline']}")
+        for r in rows.values():
+            r["roofline"] = {"bound": "mfma", "achieved": r["tflops"], "peak": PEAK_FP32_MATRIX_TFLOPS,
+                             "unit": "TFLOP/s", "frac": r["frac_peak"]}
         result["bprop_" + kind] = rows
 
     if args.sgemm:

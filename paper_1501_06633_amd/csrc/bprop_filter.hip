@@ -295,11 +295,16 @@ __device__ __forceinline__ void filter_grad_workgroup(const FilterGradParams& p,
         const bool has_next = steady || (s + 1 < ns);
         const bool refill   = steady || (s + NS - 1 < ns);
 
+        // sched_barrier(0): keep the written order of requests, waits and MFMA groups -- the MFMAs
+        // are free to move across the asm statements otherwise, and a build that sinks them below
+        // the next wait serialises LDS latency and the barrier with the matrix work
         request(uc, I1{}, I1{});
         await(IReq{}, I0{});
+        __builtin_amdgcn_sched_barrier(0);
         static_for<4>([&](auto qc) {
             constexpr int q = decltype(qc)::value;
             if constexpr (q == 1) {
+                __builtin_amdgcn_sched_barrier(0);
                 if (has_next) {
                     if constexpr (steady) {
                         vmem_wait<(NS - 3) * NL>();
@@ -312,6 +317,7 @@ __device__ __forceinline__ void filter_grad_workgroup(const FilterGradParams& p,
                     }
                     bare_barrier();
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
             static_for<NM>([&](auto mc) {
                 constexpr int mi = decltype(mc)::value, a = mi / RB, b = mi % RB;
@@ -331,8 +337,10 @@ __device__ __forceinline__ void filter_grad_workgroup(const FilterGradParams& p,
         // always the same request/await pair, also behind the last slab (where it fetches values
         // nobody uses): a branch here would let the compiler copy a fragment register on one path
         // before the wait that makes it valid
+        __builtin_amdgcn_sched_barrier(0);
         request(std::integral_constant<int, unext>{}, I0{}, I0{});
         await(IReq{}, I1{});
+        __builtin_amdgcn_sched_barrier(0);
         static_for<4>([&](auto qc) {
             constexpr int q = decltype(qc)::value;
             static_for<NM>([&](auto mc) {
@@ -340,6 +348,7 @@ __device__ __forceinline__ void filter_grad_workgroup(const FilterGradParams& p,
                 acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[1][a][q], fb[1][b][q], acc[a][b], 0, 0, 0);
             });
         });
+        __builtin_amdgcn_sched_barrier(0);
     };
     int s0 = 0;
     for (; s0 + 2 * NS - 1 < ns; s0 += NS)

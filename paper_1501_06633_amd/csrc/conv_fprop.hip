@@ -69,9 +69,10 @@ template <class V> __device__ __forceinline__ float comp(const V& v, int i)
 
 // WO x WM waves per workgroup; each wave owns RA x RB MFMA blocks of 32x32;
 // KS patch columns per slab; NS LDS stages; VW floats per global access (4 or 1).
-template <int WO_, int WM_, int RA_, int RB_, int KS_, int NS_, int VW_>
+template <int WO_, int WM_, int RA_, int RB_, int KS_, int NS_, int VW_, int JB_ = 2>
 struct Cfg {
     static constexpr int WO = WO_, WM = WM_, RA = RA_, RB = RB_, KS = KS_, NS = NS_, VW = VW_;
+    static constexpr int JB = JB_;                    // k-step of a slab in front of which the barrier sits
     static constexpr int NT = 64 * WO * WM;           // threads
     static constexpr int TO = WO * RA * 32;           // tile rows (filters)
     static constexpr int TM = WM * RB * 32;           // tile columns (flat m)
@@ -264,7 +265,7 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
     // done with slab s-1, whose stage is refilled with slab s+NS-1; the refill
     // is issued in between that k-step's MFMAs.
     constexpr int NSTEP = KS / 2;     // MFMA k-steps per slab
-    constexpr int JB    = 1;          // k-step in front of which the barrier sits
+    constexpr int JB    = C::JB;      // k-step in front of which the barrier sits
     constexpr int NM    = RA * RB;    // MFMAs per k-step
     static_assert(NSTEP % 2 == 0 && JB < NSTEP, "fragment double-buffer parity must not depend on the slab");
     static_assert((NS - 1) * STAGE_BYTES + (2 * (NSTEP - 1) * TO + (RA - 1) * 32) * 4 < 65536 &&
@@ -413,6 +414,10 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
                             }
                         }
                     });
+                    // keep the written order request / wait / MFMAs k-step by k-step: the MFMAs are
+                    // free to move across the asm statements otherwise, and a build that sinks
+                    // them below the next wait serialises LDS latency with the matrix work
+                    __builtin_amdgcn_sched_barrier(0);
                 });
             };
             int s0 = 0;
@@ -514,8 +519,8 @@ template <class C> struct PieceOf<C, 2> {
     static_assert(C::RA % 2 == 0 || (C::WO == 2 && C::RB % 2 == 0), "no way to halve this tile");
     // halve the per-wave filter blocks when possible, else the filter waves (moved to the column side)
     typedef typename std::conditional<C::RA % 2 == 0,
-        Cfg<C::WO, C::WM, C::RA / 2, C::RB, C::KS, C::NS, C::VW>,
-        Cfg<1, C::WM * 2, C::RA, C::RB / 2, C::KS, C::NS, C::VW>>::type type;
+        Cfg<C::WO, C::WM, C::RA / 2, C::RB, C::KS, C::NS, C::VW, C::JB>,
+        Cfg<1, C::WM * 2, C::RA, C::RB / 2, C::KS, C::NS, C::VW, C::JB>>::type type;
 };
 template <class C> struct PieceOf<C, 4> {
     typedef typename PieceOf<typename PieceOf<C, 2>::type, 2>::type type;
