@@ -153,6 +153,9 @@ def main():
     ap.add_argument("--bprop-filter", action="store_true",
                     help="also time the filter gradient (BPROP w.r.t. the weights) of the five layers; each call "
                          "is the partial-gradient kernel plus the kernel that sums the partials")
+    ap.add_argument("--no-bprop", action="store_true",
+                    help="leave the two gradients out of the per-layer table (they are timed by default, "
+                         "unless --no-layers)")
     ap.add_argument("--bprop-layers", default="tiny,conv1,conv2,conv3,vgg",
                     help="comma-separated layers for --bprop-data / --bprop-filter (default: all five)")
     ap.add_argument("--sgemm", action="store_true",
@@ -328,7 +331,9 @@ def main():
                 "frac_peak": round(fl / ms / 1e9 / PEAK_FP32_MATRIX_TFLOPS, 4),
                 "stride": Lb.stride, "workspace_bytes": need}
 
-    for kind, flag in (("data", args.bprop_data), ("filter", args.bprop_filter)):
+    with_table = not args.no_layers and not args.no_bprop
+    do_data, do_filter = args.bprop_data or with_table, args.bprop_filter or with_table
+    for kind, flag in (("data", do_data), ("filter", do_filter)):
         if not flag:
             continue
         rows = {}
