@@ -512,21 +512,35 @@ __device__ __forceinline__ int column_tile(const ConvParams& p, int seq)
     return y * p.row_tiles + xt;
 }
 
-// A tile cut into SPLIT pieces along the filter dimension: same columns, same
-// threads, same ring depth and slab, TO / SPLIT filters.
+// A tile cut into SPLIT pieces of equal area: same threads, same ring depth and
+// slab.  Along the filter dimension where the wave layout allows it (same
+// columns, TO / SPLIT filters); a tile with an odd number of filter blocks per
+// wave is halved along the columns instead.
 template <class C, int SPLIT> struct PieceOf;
 template <class C> struct PieceOf<C, 2> {
-    static_assert(C::RA % 2 == 0 || (C::WO == 2 && C::RB % 2 == 0), "no way to halve this tile");
-    // halve the per-wave filter blocks when possible, else the filter waves (moved to the column side)
+    static_assert(C::RA % 2 == 0 || C::RB % 2 == 0, "no way to halve this tile");
     typedef typename std::conditional<C::RA % 2 == 0,
-        Cfg<C::WO, C::WM, C::RA / 2, C::RB, C::KS, C::NS, C::VW, C::JB>,
-        Cfg<1, C::WM * 2, C::RA, C::RB / 2, C::KS, C::NS, C::VW, C::JB>>::type type;
+        Cfg<C::WO, C::WM, C::RA / 2, C::RB, C::KS, C::NS, C::VW, C::JB>,            // half the filter blocks per wave
+        typename std::conditional<C::WO == 2,
+            Cfg<1, C::WM * 2, C::RA, C::RB / 2, C::KS, C::NS, C::VW, C::JB>,        // half the filter waves, moved to the column side
+            Cfg<C::WO, C::WM, C::RA, C::RB / 2, C::KS, C::NS, C::VW, C::JB>>::type  // half the columns
+        >::type type;
 };
 template <class C> struct PieceOf<C, 4> {
     typedef typename PieceOf<typename PieceOf<C, 2>::type, 2>::type type;
 };
 
-// SPLITS: 1 = whole tiles only; 4 = the kernel also carries the half- and quarter-tile bodies.
+// Run piece `part` of the tile at (o0, m0) of the whole-tile shape C as shape P.
+template <class C, class P>
+__device__ __forceinline__ void conv_piece(const ConvParams& p, unsigned char* lds, int o0, int m0, int part)
+{
+    static_assert(P::NT == C::NT && P::TO * P::TM * (C::TO / P::TO) * (C::TM / P::TM) == C::TO * C::TM, "piece shape");
+    constexpr int along_m = C::TM / P::TM;                 // pieces side by side along the columns
+    const int pm = part % along_m, po = part / along_m;
+    conv_tile<P, 1>(p, lds, o0 + po * P::TO, m0 + pm * P::TM);
+}
+
+// SPLITS: 1 = whole tiles only; 2 = the kernel also carries the half-tile body; 4 = half and quarter.
 template <class C, int SPLITS>
 __global__ void __launch_bounds__(C::NT) conv_fprop_kernel(const ConvParams p)
 {
@@ -558,14 +572,10 @@ __global__ void __launch_bounds__(C::NT) conv_fprop_kernel(const ConvParams p)
         const int ms = tile / p.n_otiles;
         const int ot = tile - ms * p.n_otiles;
         const int mt = column_tile(p, ms);
-        if (p.split == 2) {
-            typedef typename PieceOf<C, 2>::type P2;
-            static_assert(P2::NT == C::NT && P2::TM == C::TM && 2 * P2::TO == C::TO, "half tile");
-            conv_tile<P2, 1>(p, lds_raw, ot * C::TO + part * P2::TO, mt * C::TM);
-        } else {
-            typedef typename PieceOf<C, 4>::type P4;
-            static_assert(P4::NT == C::NT && P4::TM == C::TM && 4 * P4::TO == C::TO, "quarter tile");
-            conv_tile<P4, 1>(p, lds_raw, ot * C::TO + part * P4::TO, mt * C::TM);
+        if (SPLITS == 2 || p.split == 2) {
+            conv_piece<C, typename PieceOf<C, 2>::type>(p, lds_raw, ot * C::TO, mt * C::TM, part);
+        } else if constexpr (SPLITS >= 4) {
+            conv_piece<C, typename PieceOf<C, 4>::type>(p, lds_raw, ot * C::TO, mt * C::TM, part);
         }
     }
 }
@@ -627,7 +637,7 @@ const Entry kEntries[] = {
     make_entry<C_o128m128k8, 4>("o128m128k8", 3, 0.905f, 0.870f),
     make_entry<C_o256m128>("o256m128", 1, 0.83f, 0.83f),
     make_entry<C_o128m256>("o128m256", 1, 0.83f, 0.83f),
-    make_entry<C_o96m256>("o96m256", 2, 0.860f, 0.70f),
+    make_entry<C_o96m256, 2>("o96m256", 2, 0.860f, 0.70f),
     make_entry<C_o96m128>("o96m128", 3, 0.855f, 0.855f),
     make_entry<C_o64m256>("o64m256", 2, 0.885f, 0.80f),
     make_entry<C_o32m128>("o32m128", 4, 0.80f, 0.80f),

@@ -204,6 +204,21 @@ def test_tail_pieces_bitwise(env, case, variant):
     np.testing.assert_array_equal(got, want)
 
 
+def test_tail_pieces_along_the_columns_bitwise(env):
+    """The 96x256 tile has three filter blocks per wave and is halved along the columns
+    instead: 320 tiles = one round + 64 tiles cut into 128 half pieces."""
+    _, B, oracle = env
+    Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha = 128, 34, 22, 4, 96, 3, 1, 0, 1.0
+    plan = B.mdnn_describe_launch(Nb, Wi, Hi, Nc, No, Sk, stride, pad, "o96m256")
+    say(f"[parity-tail-m] plan={plan}")
+    assert plan["tiles"] == 320 and plan["split"] == 2 and plan["pieces"] == 128
+    L = W.custom("tail_m", Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha)
+    inp, filt = W.make_int_inputs(L)
+    want = oracle.conv_fprop(inp, filt, stride, pad, alpha, want_abs=False)
+    got = run_gpu(env, L, inp, filt, "o96m256")
+    np.testing.assert_array_equal(got, want)
+
+
 def test_offsets_beyond_two_gib(env):
     """An input of 3.0 GiB (byte offsets above 2^31, close to the 4 GiB limit of the
     32-bit buffer offsets) and a padded geometry whose apron origins wrap around
