@@ -1,0 +1,46 @@
+"""Seeded random small shapes through all three entry points, integer data, bit for bit against
+the oracle: batch sizes that take the 16-byte, the per-lane and the 4-byte copy paths, filter
+counts around every tile width, strides 1-4, pads from 0 to Sk (the data gradient up to Sk-1)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_random_shapes_bitwise(seed):
+    import torch
+    from paper_1501_06633_amd import binding as B
+    import oracle
+
+    rng = np.random.default_rng(seed)
+    done = 0
+    for it in range(120):
+        Nb = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 16, 20, 32, 48, 64]))
+        Sk = int(rng.integers(1, 8))
+        stride = int(rng.integers(1, 5))
+        pad = int(rng.integers(0, Sk + 1))
+        Hi = int(rng.integers(max(1, Sk - 2 * pad), 30))
+        Wi = int(rng.integers(max(1, Sk - 2 * pad), 30))
+        Nc = int(rng.integers(1, 24))
+        No = int(rng.choice([1, 2, 3, 4, 8, 12, 31, 32, 33, 64, 65, 96, 97, 128, 130, 140]))
+        alpha = float(rng.choice([1.0, 0.5, -2.0]))
+        Wo, Ho = oracle.out_dims(Wi, Hi, Sk, stride, pad)
+        x = rng.integers(-4, 5, size=(Nc, Hi, Wi, Nb)).astype(np.float32)
+        w = rng.integers(-4, 5, size=(Nc, Sk, Sk, No)).astype(np.float32)
+        g = rng.integers(-4, 5, size=(No, Ho, Wo, Nb)).astype(np.float32)
+        d_x, d_w, d_g = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), torch.from_numpy(g).cuda()
+        what = f"seed={seed} case={it} Nb={Nb} Hi={Hi} Wi={Wi} Nc={Nc} No={No} Sk={Sk} stride={stride} pad={pad} alpha={alpha}"
+        print(what, flush=True)
+        y = B.mdnn_conv_fprop(d_x, d_w, stride, pad, alpha)
+        dw = B.mdnn_conv_bprop_filter(d_x, d_g, Sk, stride, pad, alpha)
+        dx = B.mdnn_conv_bprop_data(d_g, d_w, (Hi, Wi), stride, pad, alpha) if pad <= Sk - 1 else None
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(y.cpu().numpy(), oracle.conv_fprop(x, w, stride, pad, alpha, want_abs=False), err_msg=what)
+        np.testing.assert_array_equal(dw.cpu().numpy(), oracle.conv_bprop_filter(x, g, Sk, stride, pad, alpha, want_abs=False),
+                                      err_msg=what)
+        if dx is not None:
+            np.testing.assert_array_equal(dx.cpu().numpy(),
+                                          oracle.conv_bprop_data(g, w, (Hi, Wi), stride, pad, alpha, want_abs=False), err_msg=what)
+        done += 1
+    assert done == 120
