@@ -169,3 +169,32 @@ def test_caller_workspace_and_overwrite(env):
     torch.cuda.synchronize()
     want = oracle.conv_bprop_data(dout, filt, (L.Hi, L.Wi), L.stride, L.pad, L.alpha, want_abs=False)
     np.testing.assert_array_equal(din.cpu().numpy(), want)
+
+
+def test_result_beyond_two_gib(env):
+    """A data gradient of 3.0 GiB: the stores of the forward kernel it runs on reach byte offsets
+    above 2^31.  Sampled elements, biased to the last channels and the border, against the
+    oracle's one-by-one evaluation; integer data, exact."""
+    torch, B, oracle = env
+    Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha = 128, 64, 64, 1536, 8, 3, 1, 1, 0.5
+    say(f"[bprop-3gib] din bytes = {4 * Nb * Hi * Wi * Nc}")
+    rng = np.random.default_rng(W.SEED_BASE + 79)
+    dout = rng.integers(-3, 4, size=(No, Hi, Wi, Nb)).astype(np.float32)
+    filt = rng.integers(-3, 4, size=(Nc, Sk, Sk, No)).astype(np.float32)
+    got = B.mdnn_conv_bprop_data(torch.from_numpy(dout).cuda(), torch.from_numpy(filt).cuda(), (Hi, Wi),
+                                 stride, pad, alpha)
+    torch.cuda.synchronize()
+    npts = 20000
+    idx = np.stack([rng.integers(0, Nc, npts), rng.integers(0, Hi, npts),
+                    rng.integers(0, Wi, npts), rng.integers(0, Nb, npts)], axis=1).astype(np.int32)
+    idx[:5000, 0] = rng.integers(Nc - 40, Nc, 5000)
+    idx[5000:6000, 1] = rng.choice([0, Hi - 1], 1000)
+    idx[6000:7000, 2] = rng.choice([0, Wi - 1], 1000)
+    idx[0] = (0, 0, 0, 0)
+    idx[1] = (Nc - 1, Hi - 1, Wi - 1, Nb - 1)
+    t = torch.from_numpy(idx.astype(np.int64)).cuda()
+    sampled = got[t[:, 0], t[:, 1], t[:, 2], t[:, 3]].cpu().numpy()
+    del got
+    vals, _ = oracle.conv_bprop_data_points(dout, filt, idx, (Hi, Wi), stride, pad, alpha)
+    np.testing.assert_array_equal(sampled, vals)
+    assert np.abs(vals).max() > 0

@@ -177,3 +177,32 @@ def test_caller_workspace_overwrite_and_determinism(env):
     np.testing.assert_array_equal(again.cpu().numpy(), first)                # fixed summation order
     with pytest.raises(B.MdnnError):
         B.mdnn_conv_bprop_filter(d_in, d_g, L.Sk, L.stride, L.pad, L.alpha, workspace=ws[: need // 4 - 4])
+
+
+def test_offsets_beyond_two_gib(env):
+    """A forward input of 3.0 GiB: the patch gather of the filter gradient works with byte offsets
+    above 2^31 and with apron origins that wrap around zero.  Sampled elements of dfilt, biased to
+    the last channels and the border taps, against the oracle's one-by-one evaluation; integer
+    data with a sparse gradient so that every partial sum stays exact."""
+    torch, B, oracle = env
+    Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha = 128, 64, 64, 1536, 8, 3, 1, 1, 1.0
+    say(f"[bprop-filter-3gib] in bytes = {4 * Nb * Hi * Wi * Nc}")
+    rng = np.random.default_rng(W.SEED_BASE + 78)
+    inp = rng.integers(-2, 3, size=(Nc, Hi, Wi, Nb), dtype=np.int8).astype(np.float32)
+    dout = (rng.integers(-2, 3, size=(No, Hi, Wi, Nb)) * (rng.random((No, Hi, Wi, Nb)) < 0.25)).astype(np.float32)
+    d_in = torch.from_numpy(inp).cuda()
+    got = B.mdnn_conv_bprop_filter(d_in, torch.from_numpy(dout).cuda(), Sk, stride, pad, alpha)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    del d_in
+    npts = 1500
+    idx = np.stack([rng.integers(0, Nc, npts), rng.integers(0, Sk, npts),
+                    rng.integers(0, Sk, npts), rng.integers(0, No, npts)], axis=1).astype(np.int32)
+    idx[:500, 0] = rng.integers(Nc - 40, Nc, 500)      # offsets above 2^31 ... 3 GiB
+    idx[500:600, 0] = rng.integers(0, 2, 100)
+    idx[0] = (0, 0, 0, 0)
+    idx[1] = (Nc - 1, Sk - 1, Sk - 1, No - 1)
+    vals, _ = oracle.conv_bprop_filter_points(inp, dout, idx, Sk, stride, pad, alpha)
+    c, ky, kx, o = idx.T
+    np.testing.assert_array_equal(got[c, ky, kx, o], vals)        # |sum| <= 4 * 524288 * 0.25 << 2^24: exact
+    assert np.abs(vals).max() > 0
