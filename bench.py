@@ -185,7 +185,7 @@ def main():
 
     # ---- headline: K timed steps of the named workload
     log(f"[bench] workload={args.workload} steps={args.steps} warmup={args.warmup}")
-    rep, _ = layer_report(torch, B, W, args.workload, args.steps, args.warmup, args.variant,
+    rep, ctx = layer_report(torch, B, W, args.workload, args.steps, args.warmup, args.variant,
                           min_warm_ms=WARM_MS_FLOOR)
     L = W.LAYERS[args.workload]
     log(f"[bench] {args.workload}: {rep['ms']} ms/step, {rep['tflops']} TFLOP/s "
@@ -234,7 +234,28 @@ def main():
         ceiling = fl / (e0.elapsed_time(e1) * 1e-3) / 1e12
         result["mfma_f32_sustained_tflops"] = round(ceiling, 2)
         result["frac_of_sustained"] = round(rep["tflops"] / ceiling, 4)
-        log(f"[bench] register-only FP32 MFMA loop: {ceiling:.1f} TFLOP/s sustained")
+        # the matrix rate with every SIMD busy and no memory traffic, read as a clock:
+        # sustained FLOP/s / (CUs x 4 SIMDs x 64 FLOP per clock)
+        result["mfma_clock_equivalent_ghz"] = round(ceiling * 1e12 / (256 * 4 * 64) / 1e9, 3)
+        log(f"[bench] register-only FP32 MFMA loop: {ceiling:.1f} TFLOP/s sustained "
+            f"(= {result['mfma_clock_equivalent_ghz']} GHz on every SIMD)")
+
+    # ---- the headline workload launch by launch (one event pair each): median and minimum
+    if not args.no_layers:
+        L0, inp0, filt0, out0 = ctx
+        d_in0, d_f0 = torch.from_numpy(inp0).cuda(), torch.from_numpy(filt0).cuda()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(50)]
+        for _ in range(int(WARM_MS_FLOOR / max(rep["ms"], 1e-3)) + 1):
+            B.mdnn_conv_fprop(d_in0, d_f0, L0.stride, L0.pad, L0.alpha, out=out0, variant=args.variant)
+        for a, b in evs:
+            a.record()
+            B.mdnn_conv_fprop(d_in0, d_f0, L0.stride, L0.pad, L0.alpha, out=out0, variant=args.variant)
+            b.record()
+        torch.cuda.synchronize()
+        per = sorted(a.elapsed_time(b) for a, b in evs)
+        result["per_launch_ms"] = {"launches": 50, "median": round(per[25], 5), "min": round(per[0], 5),
+                                   "note": "one event pair per launch; includes the gap between the two events"}
+        del d_in0, d_f0
 
     # ---- the other layer shapes (same launch path, fewer steps)
     if not args.no_layers:
