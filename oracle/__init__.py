@@ -56,6 +56,8 @@ def _load():
     lib.mdnn_oracle_conv_bprop_data_points.argtypes = [p, p, p, ctypes.c_int64, p, p,
                                                        i, i, i, i, i, i, i, i, f]
     lib.mdnn_oracle_conv_bprop_data_points.restype = i
+    lib.mdnn_oracle_sgemm_tn.argtypes = [p, p, p, p, i, i, i, f, i]
+    lib.mdnn_oracle_sgemm_tn.restype = i
     lib.mdnn_oracle_conv_fprop_points.argtypes = [p, p, p, ctypes.c_int64, p, p,
                                                   i, i, i, i, i, i, i, i, f]
     lib.mdnn_oracle_conv_fprop_points.restype = i
@@ -220,3 +222,23 @@ def conv_bprop_data_points(dout, filt, idx, in_hw, stride, pad, alpha):
     if rc:
         raise ValueError("oracle rejected the arguments (index out of range?)")
     return vals, ab
+
+
+def sgemm_tn(a, b, alpha, want_abs=True, nthreads=0):
+    """a (K,N) f32, b (K,M) f32 -> c (N,M) f32 = alpha * a^T b and, when
+    ``want_abs``, the per-element sum of |products| in float64."""
+    K, N = a.shape
+    K2, M = b.shape
+    if K2 != K:
+        raise ValueError("a and b must have the same number of rows")
+    _check(a, a.shape, "a")
+    _check(b, b.shape, "b")
+    c = np.empty((N, M), dtype=np.float32)
+    ab = np.empty((N, M), dtype=np.float64) if want_abs else None
+    rc = _load().mdnn_oracle_sgemm_tn(
+        a.ctypes.data, b.ctypes.data, c.ctypes.data,
+        ab.ctypes.data if ab is not None else None,
+        N, M, K, float(alpha), int(nthreads))
+    if rc:
+        raise ValueError("oracle rejected the arguments")
+    return (c, ab) if want_abs else c

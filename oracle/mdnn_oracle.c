@@ -42,6 +42,12 @@
  * pixels of patch x gradient outer products in numpy, torch autograd in float64,
  * deltas, and planted-mistake tests.
  *
+ * The plain matrix product in the convolution's operand layout (the SGEMM
+ * the paper's conclusion measures itself against, and what a 1 x 1 filter
+ * reduces the convolution to) closes the file.  Its pins: a hand-worked
+ * case, the library's float64 matmul, identity operands, the forward function
+ * at Sk = 1, and planted mistakes.
+ *
  * Pins (tests/test_oracle_*.py, CPU only): brute-force im2col x GEMM in numpy
  * float64, the 1x1/stride-1 = plain matrix product identity, delta filters,
  * linearity in alpha / additivity, the all-ones closed form, exact-integer
@@ -425,4 +431,43 @@ int mdnn_oracle_conv_bprop_data_points(const float* dout, const float* filt,
         if (abs_val) abs_val[i] = A;
     }
     return bad;
+}
+
+/*
+ * Plain single-precision matrix product in the operand layout the convolution
+ * uses: the paper's conclusion measures the kernel against SGEMM, and with a
+ * 1 x 1 filter the per-coordinate product of Section 3 is nothing else.
+ *
+ *   a  [K][N]  fp32   (the filter matrix: row k, column o)
+ *   b  [K][M]  fp32   (the input: row k, column m)
+ *   c  [N][M]  fp32   c[o][m] = alpha * sum_k a[k][o] * b[k][m]
+ *
+ * Products and sums in double, one rounding at the end, abs_sum (nullable,
+ * [N][M] doubles) the sum of |products| as in the convolution.  Three loops
+ * o, m, k; OpenMP splits the o loop.  Returns 0, or 1 on invalid arguments.
+ */
+int mdnn_oracle_sgemm_tn(const float* a, const float* b, float* c, double* abs_sum,
+                         int N, int M, int K, float alpha, int nthreads)
+{
+    if (!a || !b || !c) return 1;
+    if (N < 1 || M < 1 || K < 1) return 1;
+#ifdef _OPENMP
+    if (nthreads <= 0) nthreads = omp_get_max_threads();
+#else
+    nthreads = 1;
+#endif
+#pragma omp parallel for num_threads(nthreads) schedule(dynamic, 1)
+    for (int o = 0; o < N; ++o) {
+        for (int m = 0; m < M; ++m) {
+            double s = 0.0, ab = 0.0;
+            for (int k = 0; k < K; ++k) {
+                double p = (double)a[(size_t)k * N + o] * (double)b[(size_t)k * M + m];
+                s += p;
+                ab += fabs(p);
+            }
+            c[(size_t)o * M + m] = (float)((double)alpha * s);
+            if (abs_sum) abs_sum[(size_t)o * M + m] = ab;
+        }
+    }
+    return 0;
 }
