@@ -162,6 +162,26 @@ mdnn_status mdnn_conv_bprop_filter(const float* in, const float* dout, float* df
                                    int Sk, int stride, int pad, float alpha, void* stream);
 
 /*
+ * Plain SGEMM in the convolution's operand layout: the yardstick the paper's
+ * conclusion (Section 4) holds its kernel against, and what Section 3's
+ * patch-times-filter-matrix product becomes for a 1 x 1 filter, where the patch
+ * is the input itself.  It runs the FPROP kernel on that degenerate geometry
+ * (one pixel, M images), so the inner loop is the convolution's own.
+ *
+ *   a  device, fp32, [K][N]   row-major (the filter matrix: row k, column o)
+ *   b  device, fp32, [K][M]   row-major (the input: row k, column m)
+ *   c  device, fp32, [N][M]   row-major, fully overwritten
+ *
+ *   c[o][m] = alpha * sum_k a[k][o] * b[k][m]          (c = alpha * a^T b)
+ *
+ * Any N, M, K >= 1; the fast kernels need N % 4 == 0 and M % 4 == 0.  b and c
+ * must each be smaller than 2^32 bytes and a smaller than 2^31 (MDNN_ETOOBIG).
+ * Same stream, ownership, alignment and error rules as mdnn_conv_fprop.
+ */
+mdnn_status mdnn_sgemm_tn(const float* a, const float* b, float* c,
+                          int N, int M, int K, float alpha, void* stream);
+
+/*
  * Describe, as one line of text, how a problem would be launched: variant, tile
  * shape, number of tiles, how the last partial round of tiles is cut into
  * smaller pieces (the other block sizes Section 3.4 proposes), grid and LDS

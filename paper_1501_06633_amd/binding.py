@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
     L.mdnn_conv_bprop_filter_workspace.restype = i
     L.mdnn_conv_bprop_filter.argtypes = [p, p, p, p, ctypes.c_size_t, i, i, i, i, i, i, i, i, f, p]
     L.mdnn_conv_bprop_filter.restype = i
+    L.mdnn_sgemm_tn.argtypes = [p, p, p, i, i, i, f, p]
+    L.mdnn_sgemm_tn.restype = i
     L.mdnn_mfma_peak_probe.argtypes = [p, i, i, i, ctypes.POINTER(ctypes.c_uint64), p]
     L.mdnn_mfma_peak_probe.restype = i
     _lib = L
@@ -146,6 +148,34 @@ def mdnn_conv_fprop(inp, filt, stride, pad, alpha=1.0, out=None, variant=None, s
     if st != MDNN_OK:
         raise MdnnError(st, "mdnn_conv_fprop")
     return out
+
+
+def mdnn_sgemm_tn(a, b, alpha=1.0, c=None, stream=None):
+    """a (K,N), b (K,M): contiguous fp32 device tensors.  Returns c (N,M) = alpha * a^T b,
+    enqueued on ``stream`` (default: torch's current stream); the caller synchronises."""
+    import torch
+
+    if not (a.is_cuda and b.is_cuda):
+        raise ValueError("mdnn_sgemm_tn needs device tensors (no CPU path exists)")
+    if a.dtype != torch.float32 or b.dtype != torch.float32:
+        raise ValueError("fp32 only")
+    if not (a.is_contiguous() and b.is_contiguous()) or a.dim() != 2 or b.dim() != 2:
+        raise ValueError("operands must be contiguous matrices")
+    K, N = a.shape
+    K2, M = b.shape
+    if K2 != K:
+        raise ValueError("a and b must have the same number of rows")
+    if c is None:
+        c = torch.empty((N, M), dtype=torch.float32, device=a.device)
+    elif tuple(c.shape) != (N, M) or c.dtype != torch.float32 or not c.is_contiguous():
+        raise ValueError("c has the wrong shape / dtype / layout")
+    if stream is None:
+        stream = torch.cuda.current_stream(a.device)
+    st = lib().mdnn_sgemm_tn(a.data_ptr(), b.data_ptr(), c.data_ptr(), N, M, K, alpha,
+                             stream.cuda_stream or None)
+    if st != MDNN_OK:
+        raise MdnnError(st, "mdnn_sgemm_tn")
+    return c
 
 
 def mdnn_conv_bprop_data_workspace(Nb, Wi, Hi, Nc, No, Sk, stride, pad):

@@ -287,6 +287,15 @@ mdnn_status mdnn_conv_fprop(const float* in, const float* filt, float* out,
                                    stream, nullptr);
 }
 
+// c (N x M) = alpha * a^T b: the 1 x 1, stride-1, unpadded convolution of one pixel of M images
+// with K channels and N filters.
+mdnn_status mdnn_sgemm_tn(const float* a, const float* b, float* c,
+                          int N, int M, int K, float alpha, void* stream)
+{
+    return mdnn_conv_fprop_variant(b, a, c, /*Nb*/ M, /*Wi*/ 1, /*Hi*/ 1, /*Nc*/ K, /*No*/ N,
+                                   /*Sk*/ 1, /*stride*/ 1, /*pad*/ 0, alpha, stream, nullptr);
+}
+
 namespace {
 
 // Geometry of the forward convolution whose stride-1 run yields the data gradient.

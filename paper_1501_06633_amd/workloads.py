@@ -112,3 +112,17 @@ def make_int_inputs(layer: Layer, lo=-4, hi=4):
     inp = rng.integers(lo, hi + 1, size=ishape).astype(np.float32)
     filt = rng.integers(lo, hi + 1, size=fshape).astype(np.float32)
     return inp, filt
+
+
+def make_matrices(N, M, K, seed, integer=False):
+    """Operands of the plain matrix product c (N x M) = alpha * a^T b: a (K,N), b (K,M), float32.
+    b is drawn like an activation (uniform in [-1, 1)), a like a filter matrix (normal, sigma 0.01);
+    with ``integer`` both hold small integers so that every fp32 partial sum is exact."""
+    rng = np.random.Generator(np.random.PCG64(SEED_BASE + seed))
+    if integer:
+        b = rng.integers(-4, 5, size=(K, M)).astype(np.float32)
+        a = rng.integers(-4, 5, size=(K, N)).astype(np.float32)
+    else:
+        b = rng.uniform(-1.0, 1.0, size=(K, M)).astype(np.float32)
+        a = rng.standard_normal(size=(K, N), dtype=np.float32) * np.float32(0.01)
+    return np.ascontiguousarray(a), np.ascontiguousarray(b)

@@ -34,7 +34,8 @@ def test_exports_every_declared_symbol(L):
     assert {"mdnn_conv_fprop", "mdnn_conv_fprop_variant", "mdnn_out_dims", "mdnn_conv_flops",
             "mdnn_status_string", "mdnn_variant_count", "mdnn_variant_name",
             "mdnn_choose_variant", "mdnn_describe_launch", "mdnn_mfma_peak_probe",
-            "mdnn_conv_bprop_data", "mdnn_conv_bprop_data_workspace"} <= set(names)
+            "mdnn_conv_bprop_data", "mdnn_conv_bprop_data_workspace",
+            "mdnn_conv_bprop_filter", "mdnn_conv_bprop_filter_workspace", "mdnn_sgemm_tn"} <= set(names)
     for n in names:
         assert hasattr(L, n), f"libmdnn.so does not export {n}"
 
@@ -194,6 +195,21 @@ def test_bprop_filter_workspace_and_argument_checks(L):
     assert call_f(wb=need - 1) == B.MDNN_EINVAL
     assert call_f(a=float("inf")) == B.MDNN_EINVAL
     assert call_f(d=FAKE + 8) == B.MDNN_EALIGN
+
+
+def test_sgemm_argument_checks(L):
+    A, Bm, C = FAKE, FAKE + 4096, FAKE + 8192
+    assert L.mdnn_sgemm_tn(None, Bm, C, 8, 8, 8, 1.0, None) == B.MDNN_ENULL
+    assert L.mdnn_sgemm_tn(A, None, C, 8, 8, 8, 1.0, None) == B.MDNN_ENULL
+    assert L.mdnn_sgemm_tn(A, Bm, None, 8, 8, 8, 1.0, None) == B.MDNN_ENULL
+    for dims in [(0, 8, 8), (8, 0, 8), (8, 8, 0), (-1, 8, 8)]:
+        assert L.mdnn_sgemm_tn(A, Bm, C, *dims, 1.0, None) == B.MDNN_EINVAL
+    assert L.mdnn_sgemm_tn(A, Bm, C, 8, 8, 8, float("nan"), None) == B.MDNN_EINVAL
+    assert L.mdnn_sgemm_tn(A + 4, Bm, C, 8, 8, 8, 1.0, None) == B.MDNN_EALIGN
+    assert L.mdnn_sgemm_tn(A, Bm, C + 8, 8, 8, 8, 1.0, None) == B.MDNN_EALIGN
+    assert L.mdnn_sgemm_tn(A, Bm, C, 8, 2**20, 2**10, 1.0, None) == B.MDNN_ETOOBIG    # b = 4 GiB
+    assert L.mdnn_sgemm_tn(A, Bm, C, 2**16, 2**14, 8, 1.0, None) == B.MDNN_ETOOBIG    # c = 4 GiB
+    assert L.mdnn_sgemm_tn(A, Bm, C, 2**15, 8, 2**14, 1.0, None) == B.MDNN_ETOOBIG    # a = 2 GiB
 
 
 def test_status_strings(L):
