@@ -610,9 +610,10 @@ struct Entry {
 };
 
 template <class C, int SPLITS = 1>
-constexpr Entry make_entry(const char* name, int wg_per_cu, float eff, float eff_few)
+constexpr Entry make_entry(const char* name, int wg_per_cu, float eff, float eff_few, int max_tab = kMaxTabEntries)
 {
-    return Entry{VariantInfo{name, C::TO, C::TM, C::KS, C::NT, C::VW == 4 ? 1 : 0, wg_per_cu, eff, eff_few, SPLITS},
+    return Entry{VariantInfo{name, C::TO, C::TM, C::KS, C::NT, C::VW == 4 ? 1 : 0, wg_per_cu, eff, eff_few, SPLITS,
+                             max_tab},
                  &conv_fprop_kernel<C, SPLITS>, C::ring_bytes};
 }
 
@@ -632,17 +633,20 @@ typedef Cfg<1, 4, 3, 1, 16, 3, 4> C_o96m128;
 
 
 const Entry kEntries[] = {
-    // name, workgroups that fit one CU, measured fraction of the matrix rate: many tiles per CU / few
+    // name, workgroups that fit one CU, measured fraction of the matrix rate: many tiles per CU / few,
+    // offset-table entries kept in LDS (sized so that a long K does not cost a resident workgroup)
     make_entry<C_o128m128, 4>("o128m128", 2, 0.900f, 0.900f),
-    make_entry<C_o128m128k8, 4>("o128m128k8", 3, 0.905f, 0.870f),
+    // 32 KB ring + 20 KB table = 52 KB: three workgroups per CU whatever K is
+    make_entry<C_o128m128k8, 4>("o128m128k8", 3, 0.905f, 0.870f, 2560),
     make_entry<C_o256m128>("o256m128", 1, 0.83f, 0.83f),
     make_entry<C_o128m256>("o128m256", 1, 0.83f, 0.83f),
-    make_entry<C_o96m256, 2>("o96m256", 2, 0.860f, 0.70f),
-    make_entry<C_o96m128>("o96m128", 3, 0.855f, 0.855f),
-    make_entry<C_o64m256>("o64m256", 2, 0.885f, 0.80f),
-    make_entry<C_o32m128>("o32m128", 4, 0.80f, 0.80f),
-    make_entry<C_o32m64>("o32m64", 8, 0.55f, 0.55f),
-    make_entry<C_o32m32>("o32m32", 8, 0.35f, 0.35f),
+    make_entry<C_o96m256, 2>("o96m256", 2, 0.860f, 0.70f, 1536),
+    // 42 KB ring + 10 KB table: three workgroups per CU whatever K is
+    make_entry<C_o96m128>("o96m128", 3, 0.855f, 0.855f, 1280),
+    make_entry<C_o64m256>("o64m256", 2, 0.885f, 0.80f, 2304),
+    make_entry<C_o32m128>("o32m128", 4, 0.80f, 0.80f, 1024),
+    make_entry<C_o32m64>("o32m64", 8, 0.55f, 0.55f, 1024),
+    make_entry<C_o32m32>("o32m32", 8, 0.35f, 0.35f, 1024),
     make_entry<C_o64m64s>("o64m64s", 4, 0.30f, 0.30f),
 };
 constexpr int kNumEntries = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
@@ -672,7 +676,7 @@ int launch_variant(int i, const ConvParams& p, void* stream)
         if (!(raised[i].load(std::memory_order_acquire) & bit)) {
             err = hipFuncSetAttribute(reinterpret_cast<const void*>(e.fn),
                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      (int)variant_lds_bytes(i, kMaxTabEntries));
+                                      (int)variant_lds_bytes(i, e.info.max_tab));
             if (err != hipSuccess) return (int)err;
             raised[i].fetch_or(bit, std::memory_order_release);
         }

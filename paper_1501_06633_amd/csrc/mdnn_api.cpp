@@ -11,7 +11,6 @@
 namespace {
 
 constexpr int     kComputeUnits = 256;          // MI355X
-using mdnn::kMaxTabEntries;
 constexpr int     kStripRows = 8;               // image rows per strip of the 2-D tile order
 constexpr int64_t kFourGiB = (int64_t)1 << 32;
 
@@ -110,7 +109,10 @@ double variant_cost(const mdnn::VariantInfo& v, int No, int64_t M)
     int n_whole, split;
     const double tail = choose_split(v, (int)tiles, &n_whole, &split);
     const double rounds = (double)(tiles / kComputeUnits) + tail;
-    const double eff = tiles < 4 * kComputeUnits ? v.eff_few : v.eff;
+    // "few": up to 4 7/8 rounds.  Measured on the 128x128 tiles: with three workgroups per compute
+    // unit, launches of 800 to 1216 tiles run at 74-85 % (the tiles beyond the first 768 land
+    // wherever slots happen to free first, two on one unit while others idle), 93 % from 1248 on.
+    const double eff = 8 * tiles < 39 * kComputeUnits ? v.eff_few : v.eff;
     return rounds * v.tile_o * v.tile_m / eff;
 }
 
@@ -182,7 +184,7 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
         }
     }
     const int kpad = div_up(g.K, vi.kslab) * vi.kslab;
-    p.tab_cap = kpad < kMaxTabEntries ? kpad : kMaxTabEntries;
+    p.tab_cap = kpad < vi.max_tab ? kpad : vi.max_tab;
     p.in_bytes = (uint32_t)g.in_bytes;
     p.filt_bytes = (uint32_t)g.filt_bytes;
     p.alpha = 0.0f;

@@ -60,6 +60,7 @@ struct VariantInfo {
     float eff_few;       // same with fewer than four tiles per compute unit: start-up and drain of
                          // co-resident workgroups coincide instead of overlapping (measured)
     int max_split;       // 1, 2 or 4: finest cut of a tile this variant's kernel can run
+    int max_tab;         // most offset-table entries kept in LDS at once (longer K: several fills per tile)
 };
 
 int                variant_count();
