@@ -112,7 +112,13 @@ double variant_cost(const mdnn::VariantInfo& v, int No, int64_t M)
     // "few": up to 4 7/8 rounds.  Measured on the 128x128 tiles: with three workgroups per compute
     // unit, launches of 800 to 1216 tiles run at 74-85 % (the tiles beyond the first 768 land
     // wherever slots happen to free first, two on one unit while others idle), 93 % from 1248 on.
-    const double eff = 8 * tiles < 39 * kComputeUnits ? v.eff_few : v.eff;
+    double eff = 8 * tiles < 39 * kComputeUnits ? v.eff_few : v.eff;
+    // More than two whole rounds that are all resident from the start (three workgroups per unit)
+    // are spread evenly by the dispatcher whatever the tiles' individual durations; with two per
+    // unit the third round starts on whichever units finish first (5x5 layer, 730 tiles of unequal
+    // apron work: 77 % against 88 %).
+    if (split == 1 && tiles > 2 * kComputeUnits && tiles <= (int64_t)v.est_wg_per_cu * kComputeUnits)
+        eff = v.eff;
     return rounds * v.tile_o * v.tile_m / eff;
 }
 
