@@ -33,7 +33,7 @@ WARM_MS_FLOOR = 100.0
 # for a plain 256 MiB device copy in the same run (--copy-calibration): factor 2.000 for
 # FETCH_SIZE, 1.000 for WRITE_SIZE.  Not measurable from inside this script; the summary with the
 # commands is profiles/conv_fprop_hbm_traffic_pmc.txt.
-MEASURED_TRAFFIC_BYTES = {"vgg": 785.4e6, "conv1": 304.2e6, "conv2": 322.1e6, "conv3": 108.2e6}
+MEASURED_TRAFFIC_BYTES = {"vgg": 783.8e6, "conv1": 305.3e6, "conv2": 322.3e6, "conv3": 108.5e6}
 
 
 def log(*a):
@@ -140,6 +140,8 @@ def main():
     ap.add_argument("--no-layers", action="store_true", help="skip the per-layer table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true", help="skip the register-only MFMA ceiling")
+    ap.add_argument("--minibatch", action="store_true",
+                    help="time the headline layer's geometry at minibatch sizes 4 ... 256")
     ap.add_argument("--block-sizes", action="store_true",
                     help="time the headline workload with every 16-byte tile variant: the block-size "
                          "experiment Section 3.4 of the paper asks for")
@@ -288,6 +290,20 @@ def main():
             log(f"[bench] block {v:11s} tile {plan['tile']:8s} {r['ms']:8.4f} ms {r['tflops']:7.2f} TFLOP/s "
                 f"{100 * r['frac_peak']:5.1f}%  L2->LDS {rows[v]['l2_to_lds_TBps']:.2f} TB/s")
         result["block_sizes"] = rows
+
+    if args.minibatch:
+        # the headline layer's geometry at other minibatch sizes (Section 3.4 of the paper: its kernel
+        # exists for minibatches of 64 and 128 only); flat-column tiles take any multiple of 4
+        rows = {}
+        for nb in (4, 8, 16, 32, 64, 128, 256):
+            name = f"{args.workload}_nb{nb}"
+            W.LAYERS[name] = W.custom(name, nb, L.Hi, L.Wi, L.Nc, L.No, L.Sk, L.stride, L.pad, L.alpha)
+            r, _ = layer_report(torch, B, W, name, 30, 5, None, min_warm_ms=WARM_MS_FLOOR)
+            del W.LAYERS[name]
+            rows[str(nb)] = {"ms": r["ms"], "tflops": r["tflops"], "frac_peak": r["frac_peak"], "variant": r["variant"]}
+            log(f"[bench] minibatch {nb:4d}: {r['ms']:8.4f} ms {r['tflops']:7.2f} TFLOP/s "
+                f"{100 * r['frac_peak']:5.1f}%  variant={r['variant']}")
+        result["minibatch"] = rows
 
     if args.rotating:
         inp, filt = W.make_inputs(L)
