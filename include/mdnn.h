@@ -121,7 +121,9 @@ const char* mdnn_choose_variant(int Nb, int Wi, int Hi, int Nc, int No,
  * (iy + pad, ix + pad) modulo the stride; every class is a stride-1 problem with
  * a ceil(Sk/stride)^2 sub-filter, and all classes run as one convolution).  It
  * may be reused or freed once the stream has passed this call.  Same stream,
- * ownership and error rules as mdnn_conv_fprop.
+ * ownership and error rules as mdnn_conv_fprop, with one difference: the call
+ * enqueues two or three kernels, and MDNN_ELAUNCH can be returned after the
+ * first of them was enqueued (din and the workspace are then undefined).
  */
 mdnn_status mdnn_conv_bprop_data_workspace(int Nb, int Wi, int Hi, int Nc, int No,
                                            int Sk, int stride, int pad, size_t* bytes);
@@ -151,7 +153,8 @@ mdnn_status mdnn_conv_bprop_data(const float* dout, const float* filt, float* di
  * is cut into ranges so that the launch fills the chip, every range leaves a
  * partial gradient there, and a second kernel adds them in a fixed order (the
  * result is deterministic).  It may be reused or freed once the stream has
- * passed this call.  Same stream, ownership and error rules as mdnn_conv_fprop;
+ * passed this call.  Same stream, ownership and error rules as mdnn_conv_fprop
+ * (two kernels: MDNN_ELAUNCH can be returned after the first was enqueued);
  * in and dout must each be smaller than 2^32 bytes (MDNN_ETOOBIG).
  */
 mdnn_status mdnn_conv_bprop_filter_workspace(int Nb, int Wi, int Hi, int Nc, int No,
