@@ -121,6 +121,34 @@ def test_variant_registry_and_choice(L):
     assert B.mdnn_choose_variant(8, 2, 2, 1, 1, 3, 1, 0) is None          # invalid geometry
 
 
+def test_choice_between_the_two_128x128_tiles_follows_the_tile_count(L):
+    """128 images per pixel, 256 filters: 2 * Hi * 16 tiles of 128x128.  The three-per-CU tile takes
+    whole rounds that are all resident (513..768 tiles) and launches of 1248 tiles or more; the
+    two-per-CU tile takes what lies between, where the other was measured at 74-85 %."""
+    pick = lambda Hi: B.mdnn_choose_variant(128, 16, Hi, 256, 256, 3, 1, 1)
+    tiles = lambda Hi: B.mdnn_describe_launch(128, 16, Hi, 256, 256, 3, 1, 1, "o128m128")["tiles"]
+    assert tiles(24) == 768 and pick(24) == "o128m128k8"        # all resident, no tail
+    assert tiles(23) == 736 and pick(23) == "o128m128k8"
+    for Hi in (26, 31, 32, 36, 38):                             # 832 ... 1216 tiles
+        assert 768 < tiles(Hi) < 1248 and pick(Hi) == "o128m128", Hi
+    for Hi in (39, 40, 48, 80):                                 # 1248 tiles and more
+        assert pick(Hi) == "o128m128k8", Hi
+    assert pick(8) == "o128m128"                                # one round
+
+
+def test_long_k_keeps_the_resident_workgroups(L):
+    """The offset table is capped per variant so that LDS use, and with it the number of
+    workgroups per CU, does not depend on K."""
+    for v, per_cu in (("o128m128k8", 3), ("o128m128", 2), ("o96m128", 3), ("o96m256", 2), ("o64m256", 2),
+                      ("o32m128", 4)):
+        short = B.mdnn_describe_launch(128, 14, 14, 64, 192, 3, 1, 1, v)
+        long_ = B.mdnn_describe_launch(128, 14, 14, 1024, 192, 3, 1, 1, v)
+        assert long_["lds_bytes"] * per_cu <= 160 * 1024, v
+        assert long_["lds_bytes"] * (per_cu + 1) > 160 * 1024 or v.startswith("o32"), v
+        assert long_["table_entries"] % long_["kslab"] == 0 and long_["table_entries"] < 9216
+        assert short["table_entries"] == 576
+
+
 def test_describe_launch(L):
     d = B.mdnn_describe_launch(64, 56, 56, 256, 256, 3, 1, 1)
     assert d["K"] == 2304 and d["M"] == 56 * 56 * 64
