@@ -1,7 +1,7 @@
 """GPU parity of the data gradient (BPROP w.r.t. the input) against the oracle,
 through the C ABI.  Same acceptance bound as the forward path: per element
 |gpu - oracle| <= 1e-4 * |alpha| * A (A = sum of |products|), exactly 0 where
-A == 0, plus the 2e-5 regression bound; integer data bit for bit."""
+A == 0, plus the 5e-6 regression bound; integer data bit for bit."""
 import sys
 
 import numpy as np
@@ -11,7 +11,7 @@ from paper_1501_06633_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
 
-LOOSE, TIGHT = 1e-4, 2e-5
+LOOSE, TIGHT = 1e-4, 5e-6
 
 
 @pytest.fixture(scope="module")

@@ -20,7 +20,7 @@ from paper_1501_06633_amd import workloads as W
 pytestmark = pytest.mark.gpu
 
 LOOSE = 1e-4
-TIGHT = 2e-5
+TIGHT = 5e-6
 
 
 @pytest.fixture(scope="module")
