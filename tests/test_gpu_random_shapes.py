@@ -44,3 +44,37 @@ def test_random_shapes_bitwise(seed):
                                           oracle.conv_bprop_data(g, w, (Hi, Wi), stride, pad, alpha, want_abs=False), err_msg=what)
         done += 1
     assert done == 120
+
+
+def test_long_contractions_every_variant_bitwise():
+    """Forty seeded shapes with K = Nc*Sk*Sk between 700 and 7000 (beyond every variant's LDS
+    table, so the contraction is walked in several table fills) on small images, through every
+    tile variant: integer data, bit for bit against the oracle."""
+    import torch
+    from paper_1501_06633_amd import binding as B
+    import oracle
+
+    rng = np.random.default_rng(2025)
+    runs = 0
+    for it in range(40):
+        Nb = int(rng.choice([4, 8, 12, 16, 32, 64]))
+        Sk = int(rng.choice([1, 2, 3, 5]))
+        stride = int(rng.integers(1, 3))
+        pad = int(rng.integers(0, Sk))
+        Hi = int(rng.integers(Sk, 9))
+        Wi = int(rng.integers(Sk, 9))
+        Nc = max(1, int(rng.integers(700, 7000)) // (Sk * Sk))
+        No = int(rng.choice([4, 32, 36, 64, 96, 100, 128, 192, 260]))
+        alpha = float(rng.choice([1.0, 0.5]))
+        x = rng.integers(-4, 5, size=(Nc, Hi, Wi, Nb)).astype(np.float32)
+        w = rng.integers(-4, 5, size=(Nc, Sk, Sk, No)).astype(np.float32)
+        want = oracle.conv_fprop(x, w, stride, pad, alpha, want_abs=False)
+        d_x, d_w = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+        what = f"case={it} Nb={Nb} Hi={Hi} Wi={Wi} Nc={Nc} No={No} Sk={Sk} stride={stride} pad={pad} alpha={alpha}"
+        print(what, flush=True)
+        for v in B.mdnn_variant_names():
+            y = B.mdnn_conv_fprop(d_x, d_w, stride, pad, alpha, variant=v)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(y.cpu().numpy(), want, err_msg=f"{what} variant={v}")
+            runs += 1
+    assert runs == 40 * len(B.mdnn_variant_names())
