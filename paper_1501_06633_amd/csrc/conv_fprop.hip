@@ -548,14 +548,18 @@ __global__ void __launch_bounds__(C::NT) conv_fprop_kernel(const ConvParams p)
     // ---- tile map.  Workgroups are dealt round-robin to the 8 XCDs, each with
     // its own L2: give every XCD a contiguous run of tiles so that neighbouring
     // output coordinates (overlapping patches) and the filter tiles of one
-    // coordinate (same patch) meet in the same L2.  Whole tiles come first in
-    // launch order; the pieces of the last, partial round of tiles follow, so
-    // that the tail of the launch is made of short workgroups on every CU
-    // instead of long ones on a few (Section 3.4's smaller blocks, used only
-    // where they pay).
-    const int bid   = blockIdx.x;
+    // coordinate (same patch) meet in the same L2.  Launch order: up to one
+    // piece per CU, then the whole tiles, then the remaining pieces of the
+    // last, partial round of tiles -- so that the tail of the launch is made of
+    // short workgroups on every CU instead of long ones on a few (Section 3.4's
+    // smaller blocks, used only where they pay), and so that the workgroups
+    // sharing a CU start their whole tiles a fraction of a tile apart (see the
+    // host's plan()).  Every region is a multiple of 8 workgroups long, which
+    // keeps workgroup id mod 8 = XCD.
+    const int front = 8 * p.first_per_xcd;
     const int whole = 8 * p.tiles_per_xcd;
-    if (bid < whole) {
+    const int bid   = (int)blockIdx.x - front;
+    if (bid >= 0 && bid < whole) {
         const int tile = (bid & 7) * p.tiles_per_xcd + (bid >> 3);
         if (tile >= p.n_whole) return;                       // uniform per workgroup
         const int ms = tile / p.n_otiles;
@@ -564,9 +568,16 @@ __global__ void __launch_bounds__(C::NT) conv_fprop_kernel(const ConvParams p)
         return;
     }
     if constexpr (SPLITS > 1) {
-        const int b     = bid - whole;
-        const int piece = (b & 7) * p.pieces_per_xcd + (b >> 3);
-        if (piece >= p.n_pieces) return;
+        int piece;
+        if (bid < 0) {
+            const int b = (int)blockIdx.x;
+            piece = (b & 7) * p.first_per_xcd + (b >> 3);
+            if (piece >= p.n_first) return;
+        } else {
+            const int b = bid - whole;
+            piece = p.n_first + (b & 7) * p.last_per_xcd + (b >> 3);
+            if (piece >= p.n_pieces) return;
+        }
         const int tile = p.n_whole + piece / p.split;
         const int part = piece - (piece / p.split) * p.split;
         const int ms = tile / p.n_otiles;
@@ -681,7 +692,7 @@ int launch_variant(int i, const ConvParams& p, void* stream)
             raised[i].fetch_or(bit, std::memory_order_release);
         }
     }
-    const dim3 grid((unsigned)(8 * p.tiles_per_xcd + 8 * p.pieces_per_xcd)), block((unsigned)e.info.threads);
+    const dim3 grid((unsigned)(8 * (p.first_per_xcd + p.tiles_per_xcd + p.last_per_xcd))), block((unsigned)e.info.threads);
     hipLaunchKernelGGL(e.fn, grid, block, lds, static_cast<hipStream_t>(stream), p);
     err = hipGetLastError();
     return (int)err;

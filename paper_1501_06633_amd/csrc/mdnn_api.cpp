@@ -176,8 +176,16 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
     p.n_tiles = (int)n_tiles;
     choose_split(vi, p.n_tiles, &p.n_whole, &p.split);
     p.n_pieces = (p.n_tiles - p.n_whole) * p.split;
+    // Pieces go last, where the dispatcher deals them to whichever units free up first -- except
+    // up to one per unit, which go FIRST: the workgroups that share a unit then start their whole
+    // tiles a fraction of a tile apart and stay out of step, so one's prologue and epilogue overlap
+    // the others' matrix work instead of coinciding with theirs (measured: +0.8 % on the 3x3
+    // 256-channel layer, +1 ... +2.4 % on 512-channel layers; -0.6 % with a single round of whole
+    // tiles, hence the condition).
+    p.n_first = p.n_whole >= 2 * kComputeUnits ? std::min(p.n_pieces, kComputeUnits) : 0;
+    p.first_per_xcd = div_up(p.n_first, 8);
+    p.last_per_xcd = div_up(p.n_pieces - p.n_first, 8);
     p.tiles_per_xcd = div_up(p.n_whole, 8);
-    p.pieces_per_xcd = div_up(p.n_pieces, 8);
     // 2-D visiting order of the column tiles (see ConvParams): needs tiles aligned with pixel rows
     p.row_tiles = 0;
     p.strip_rows = 1;
@@ -280,9 +288,9 @@ mdnn_status mdnn_describe_launch(int Nb, int Wi, int Hi, int Nc, int No, int Sk,
     const mdnn::VariantInfo& vi = mdnn::variant_info(v);
     std::snprintf(text, text_size,
                   "variant=%s tile=%dx%d kslab=%d threads=%d K=%d M=%d tiles=%d whole=%d split=%d pieces=%d "
-                  "grid=%d lds_bytes=%u table_entries=%d",
+                  "pieces_first=%d grid=%d lds_bytes=%u table_entries=%d",
                   vi.name, vi.tile_o, vi.tile_m, vi.kslab, vi.threads, p.K, p.M, p.n_tiles, p.n_whole,
-                  p.split, p.n_pieces, 8 * p.tiles_per_xcd + 8 * p.pieces_per_xcd,
+                  p.split, p.n_pieces, p.n_first, 8 * (p.first_per_xcd + p.tiles_per_xcd + p.last_per_xcd),
                   mdnn::variant_lds_bytes(v, p.tab_cap), p.tab_cap);
     return MDNN_OK;
 }

@@ -33,7 +33,9 @@ struct ConvParams {
     int split;
     int n_pieces;        // (n_tiles - n_whole) * split
     int tiles_per_xcd;   // ceil(n_whole / 8)
-    int pieces_per_xcd;  // ceil(n_pieces / 8)
+    int n_first;         // pieces [0, n_first) are launched before the whole tiles, the others after them
+    int first_per_xcd;   // ceil(n_first / 8)
+    int last_per_xcd;    // ceil((n_pieces - n_first) / 8)
     // Column-tile order.  When a tile covers whole output pixels and a row of pixels is a whole
     // number of tiles (row_tiles > 0), column tiles are visited in strips of strip_rows image rows,
     // column by column inside a strip, so that the tiles in flight on one XCD form a compact 2-D
