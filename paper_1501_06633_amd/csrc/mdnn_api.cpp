@@ -109,16 +109,22 @@ double variant_cost(const mdnn::VariantInfo& v, int No, int64_t M)
     int n_whole, split;
     const double tail = choose_split(v, (int)tiles, &n_whole, &split);
     const double rounds = (double)(tiles / kComputeUnits) + tail;
-    // "few": up to 4 7/8 rounds.  Measured on the 128x128 tiles: with three workgroups per compute
-    // unit, launches of 800 to 1216 tiles run at 74-85 % (the tiles beyond the first 768 land
-    // wherever slots happen to free first, two on one unit while others idle), 93 % from 1248 on.
-    double eff = 8 * tiles < 39 * kComputeUnits ? v.eff_few : v.eff;
-    // More than two whole rounds that are all resident from the start (three workgroups per unit)
-    // are spread evenly by the dispatcher whatever the tiles' individual durations; with two per
-    // unit the third round starts on whichever units finish first (5x5 layer, 730 tiles of unequal
-    // apron work: 77 % against 88 %).
-    if (split == 1 && tiles > 2 * kComputeUnits && tiles <= (int64_t)v.est_wg_per_cu * kComputeUnits)
-        eff = v.eff;
+    // Which of the two measured efficiencies applies.  Tiles that hold two workgroups per unit: "few"
+    // means fewer than 4 7/8 rounds.  Tiles that hold three: more than two rounds count as many,
+    // except when the whole tiles fill the 768 slots once and a part of them a second time with
+    // fewer than one piece per unit in front of them (the tiles beyond the first 768 then land
+    // wherever slots free first, two on one unit while others idle: 73-82 % at 992 ... 1120 tiles
+    // against 93 % at 768, at 1088 with 256 pieces in front, and from 1248 on).
+    const int64_t n_pieces = (tiles - n_whole) * split;
+    bool few;
+    if (v.est_wg_per_cu >= 3) {
+        const bool partial_second_wave = n_whole > 3 * kComputeUnits && 8 * (int64_t)n_whole < 39 * kComputeUnits &&
+                                         n_pieces < kComputeUnits;
+        few = tiles <= 2 * kComputeUnits || partial_second_wave;
+    } else {
+        few = 8 * tiles < 39 * kComputeUnits;
+    }
+    const double eff = few ? v.eff_few : v.eff;
     return rounds * v.tile_o * v.tile_m / eff;
 }
 

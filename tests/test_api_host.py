@@ -123,17 +123,23 @@ def test_variant_registry_and_choice(L):
 
 def test_choice_between_the_two_128x128_tiles_follows_the_tile_count(L):
     """128 images per pixel, 256 filters: 2 * Hi * 16 tiles of 128x128.  The three-per-CU tile takes
-    whole rounds that are all resident (513..768 tiles) and launches of 1248 tiles or more; the
-    two-per-CU tile takes what lies between, where the other was measured at 74-85 %."""
+    every launch of more than two rounds except those whose whole tiles fill the 768 slots once and
+    partly a second time with fewer than 256 pieces in front (measured at 73-82 %); the two-per-CU
+    tile takes those and everything up to two rounds."""
     pick = lambda Hi: B.mdnn_choose_variant(128, 16, Hi, 256, 256, 3, 1, 1)
-    tiles = lambda Hi: B.mdnn_describe_launch(128, 16, Hi, 256, 256, 3, 1, 1, "o128m128")["tiles"]
-    assert tiles(24) == 768 and pick(24) == "o128m128k8"        # all resident, no tail
-    assert tiles(23) == 736 and pick(23) == "o128m128k8"
-    for Hi in (26, 31, 32, 36, 38):                             # 832 ... 1216 tiles
-        assert 768 < tiles(Hi) < 1248 and pick(Hi) == "o128m128", Hi
+    plan = lambda Hi: B.mdnn_describe_launch(128, 16, Hi, 256, 256, 3, 1, 1, "o128m128k8")
+    for Hi in (8, 12, 16):                                      # up to two rounds
+        assert plan(Hi)["tiles"] <= 512 and pick(Hi) == "o128m128", Hi
+    for Hi in (18, 23, 24, 26, 28):                             # 576 ... 896 tiles: at most 768 whole ones
+        assert plan(Hi)["whole"] <= 768 and pick(Hi) == "o128m128k8", Hi
+    for Hi in (31, 32, 33, 35):                                 # 992, 1024, 1056, 1120 tiles
+        d = plan(Hi)
+        assert 768 < d["whole"] < 1248 and d["pieces"] < 256 and pick(Hi) == "o128m128", Hi
+    for Hi in (34, 36):                                         # 1088, 1152 tiles: 1024 whole + 256 pieces in front
+        d = plan(Hi)
+        assert d["whole"] == 1024 and d["pieces_first"] == 256 and pick(Hi) == "o128m128k8", Hi
     for Hi in (39, 40, 48, 80):                                 # 1248 tiles and more
         assert pick(Hi) == "o128m128k8", Hi
-    assert pick(8) == "o128m128"                                # one round
 
 
 def test_long_k_keeps_the_resident_workgroups(L):
