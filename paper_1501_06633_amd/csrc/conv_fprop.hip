@@ -651,7 +651,7 @@ const Entry kEntries[] = {
     make_entry<C_o128m128k8, 4>("o128m128k8", 3, 0.905f, 0.870f, 2560),
     make_entry<C_o256m128>("o256m128", 1, 0.83f, 0.83f),
     make_entry<C_o128m256>("o128m256", 1, 0.83f, 0.83f),
-    make_entry<C_o96m256, 2>("o96m256", 2, 0.860f, 0.70f, 1536),
+    make_entry<C_o96m256, 2>("o96m256", 2, 0.860f, 0.80f, 1536),
     // 42 KB ring + 10 KB table: three workgroups per CU whatever K is
     make_entry<C_o96m128>("o96m128", 3, 0.855f, 0.855f, 1280),
     make_entry<C_o64m256>("o64m256", 2, 0.885f, 0.80f, 2304),

@@ -110,21 +110,24 @@ double variant_cost(const mdnn::VariantInfo& v, int No, int64_t M)
     const double tail = choose_split(v, (int)tiles, &n_whole, &split);
     const double rounds = (double)(tiles / kComputeUnits) + tail;
     // Which of the two measured efficiencies applies.  Tiles that hold two workgroups per unit: "few"
-    // means fewer than 4 7/8 rounds.  Tiles that hold three: more than two rounds count as many,
-    // except when the whole tiles fill the 768 slots once and a part of them a second time with
-    // fewer than one piece per unit in front of them (the tiles beyond the first 768 then land
-    // wherever slots free first, two on one unit while others idle: 73-82 % at 992 ... 1120 tiles
-    // against 93 % at 768, at 1088 with 256 pieces in front, and from 1248 on).
+    // means fewer than 4 7/8 rounds.  Tiles that hold three or more: more than two rounds count as
+    // many.  Exception for three per unit: when the whole tiles fill the 768 slots once and a part
+    // of them a second time (up to 1248) with fewer than one piece per unit in front of them, the
+    // tiles beyond the first wave land wherever slots free first, two on one unit while others
+    // idle.  128x128: 73-82 % at 992 ... 1120 tiles against 93 % at 768, at 1088 with 256 pieces in
+    // front, and from 1248 on; 96x128: 91 % at 768 tiles, 74 % at 1024.  (The small tiles at four
+    // and more per unit show no such dip: 32x128 follows plain rounds of 256.)
     const int64_t n_pieces = (tiles - n_whole) * split;
-    bool few;
+    double eff;
     if (v.est_wg_per_cu >= 3) {
-        const bool partial_second_wave = n_whole > 3 * kComputeUnits && 8 * (int64_t)n_whole < 39 * kComputeUnits &&
+        const int64_t slots = 3 * kComputeUnits;
+        const bool partial_second_wave = v.est_wg_per_cu == 3 && n_whole > slots && 8 * (int64_t)n_whole < 13 * slots &&
                                          n_pieces < kComputeUnits;
-        few = tiles <= 2 * kComputeUnits || partial_second_wave;
+        eff = tiles <= 2 * kComputeUnits ? v.eff_few : v.eff;
+        if (partial_second_wave) eff = 0.82 * v.eff_few;
     } else {
-        few = 8 * tiles < 39 * kComputeUnits;
+        eff = 8 * tiles < 39 * kComputeUnits ? v.eff_few : v.eff;
     }
-    const double eff = few ? v.eff_few : v.eff;
     return rounds * v.tile_o * v.tile_m / eff;
 }
 
