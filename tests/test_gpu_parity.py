@@ -219,6 +219,26 @@ def test_tail_pieces_along_the_columns_bitwise(env):
     np.testing.assert_array_equal(got, want)
 
 
+@pytest.mark.parametrize("variant,No,want_plan", [
+    ("o128m128k8", 768, dict(tiles=588, whole=512, split=2, pieces=152, pieces_first=152)),   # all pieces in front
+    ("o128m128", 1280, dict(tiles=910, whole=768, split=4, pieces=568, pieces_first=256)),    # 256 in front, 312 behind
+])
+def test_pieces_before_and_after_the_whole_tiles_bitwise(env, variant, No, want_plan):
+    """With two or more rounds of whole tiles, up to one piece per CU is launched before them and
+    the rest after them; every piece and every tile must still be computed exactly once."""
+    _, B, oracle = env
+    Nb, Hi, Wi, Nc, Sk, stride, pad, alpha = 64, (14 if No == 768 else 13), 14, 8, 3, 1, 1, 0.5
+    plan = B.mdnn_describe_launch(Nb, Wi, Hi, Nc, No, Sk, stride, pad, variant)
+    say(f"[parity-front-pieces] plan={plan}")
+    for k, v in want_plan.items():
+        assert plan[k] == v, (k, plan)
+    L = W.custom("front_pieces", Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha)
+    inp, filt = W.make_int_inputs(L)
+    want = oracle.conv_fprop(inp, filt, stride, pad, alpha, want_abs=False)
+    got = run_gpu(env, L, inp, filt, variant)
+    np.testing.assert_array_equal(got, want)
+
+
 def test_offsets_beyond_two_gib(env):
     """An input of 3.0 GiB (byte offsets above 2^31, close to the 4 GiB limit of the
     32-bit buffer offsets) and a padded geometry whose apron origins wrap around
