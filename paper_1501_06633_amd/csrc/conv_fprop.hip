@@ -552,10 +552,10 @@ __global__ void __launch_bounds__(C::NT) conv_fprop_kernel(const ConvParams p)
     // piece per CU, then the whole tiles, then the remaining pieces of the
     // last, partial round of tiles -- so that the tail of the launch is made of
     // short workgroups on every CU instead of long ones on a few (Section 3.4's
-    // smaller blocks, used only where they pay), and so that the workgroups
-    // sharing a CU start their whole tiles a fraction of a tile apart (see the
-    // host's plan()).  Every region is a multiple of 8 workgroups long, which
-    // keeps workgroup id mod 8 = XCD.
+    // smaller blocks, used only where they pay), and so that, where one piece
+    // per CU is all there is, no piece runs alone on its CU (see the host's
+    // plan()).  Every region is a multiple of 8 workgroups long, which keeps
+    // workgroup id mod 8 = XCD.
     const int front = 8 * p.first_per_xcd;
     const int whole = 8 * p.tiles_per_xcd;
     const int bid   = (int)blockIdx.x - front;

@@ -186,11 +186,11 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
     choose_split(vi, p.n_tiles, &p.n_whole, &p.split);
     p.n_pieces = (p.n_tiles - p.n_whole) * p.split;
     // Pieces go last, where the dispatcher deals them to whichever units free up first -- except
-    // up to one per unit, which go FIRST: the workgroups that share a unit then start their whole
-    // tiles a fraction of a tile apart and stay out of step, so one's prologue and epilogue overlap
-    // the others' matrix work instead of coinciding with theirs (measured: +0.8 % on the 3x3
-    // 256-channel layer, +1 ... +2.4 % on 512-channel layers; -0.6 % with a single round of whole
-    // tiles, hence the condition).
+    // up to one per unit, which go FIRST.  A piece launched last runs alone on its unit, and a lone
+    // small workgroup leaves the matrix pipe idle during every other instruction; launched first it
+    // shares the unit with whole tiles, and the launch ends with whole tiles finishing together
+    // (measured: +0.8 % on the 3x3 256-channel layer, +1 ... +3.4 % on layers with two to six rounds
+    // of tiles; -0.6 % with a single round of whole tiles, hence the condition).
     p.n_first = p.n_whole >= 2 * kComputeUnits ? std::min(p.n_pieces, kComputeUnits) : 0;
     p.first_per_xcd = div_up(p.n_first, 8);
     p.last_per_xcd = div_up(p.n_pieces - p.n_first, 8);
