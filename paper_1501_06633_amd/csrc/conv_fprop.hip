@@ -537,7 +537,7 @@ __device__ __forceinline__ void conv_piece(const ConvParams& p, unsigned char* l
     static_assert(P::NT == C::NT && P::TO * P::TM * (C::TO / P::TO) * (C::TM / P::TM) == C::TO * C::TM, "piece shape");
     constexpr int along_m = C::TM / P::TM;                 // pieces side by side along the columns
     const int pm = part % along_m, po = part / along_m;
-    conv_tile<P, 1>(p, lds, o0 + po * P::TO, m0 + pm * P::TM);
+    conv_tile<P, C::TO * 4096 + C::TM>(p, lds, o0 + po * P::TO, m0 + pm * P::TM);     // one CONTEXT per parent shape
 }
 
 // SPLITS: 1 = whole tiles only; 2 = the kernel also carries the half-tile body; 4 = half and quarter.
@@ -640,6 +640,7 @@ typedef Cfg<1, 1, 1, 1, 16, 3, 4> C_o32m32;
 typedef Cfg<2, 2, 1, 1, 16, 3, 1> C_o64m64s;
 typedef Cfg<2, 2, 2, 2, 8, 4, 4> C_o128m128k8;
 typedef Cfg<1, 4, 3, 1, 16, 3, 4> C_o96m128;
+typedef Cfg<1, 4, 2, 2, 8, 4, 4> C_o64m256k8;
 
 
 
@@ -654,7 +655,9 @@ const Entry kEntries[] = {
     make_entry<C_o96m256, 2>("o96m256", 2, 0.860f, 0.80f, 1536),
     // 42 KB ring + 10 KB table: three workgroups per CU whatever K is
     make_entry<C_o96m128>("o96m128", 3, 0.855f, 0.855f, 1280),
-    make_entry<C_o64m256>("o64m256", 2, 0.885f, 0.80f, 2304),
+    make_entry<C_o64m256>("o64m256", 2, 0.885f, 0.86f, 2304),
+    // 40 KB ring + 12 KB table: three workgroups per CU (+1 ... 2 % on 64-filter layers with many tiles)
+    make_entry<C_o64m256k8, 4>("o64m256k8", 3, 0.900f, 0.85f, 1536),
     make_entry<C_o32m128>("o32m128", 4, 0.80f, 0.80f, 1024),
     make_entry<C_o32m64>("o32m64", 8, 0.55f, 0.55f, 1024),
     make_entry<C_o32m32>("o32m32", 8, 0.35f, 0.35f, 1024),
