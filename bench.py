@@ -33,7 +33,7 @@ WARM_MS_FLOOR = 100.0
 # for a plain 256 MiB device copy in the same run (--copy-calibration): factor 2.000 for
 # FETCH_SIZE, 1.000 for WRITE_SIZE.  Not measurable from inside this script; the summary with the
 # commands is profiles/conv_fprop_hbm_traffic_pmc.txt.
-MEASURED_TRAFFIC_BYTES = {"vgg": 758.2e6, "conv1": 306.0e6, "conv2": 315.1e6, "conv3": 108.1e6}
+MEASURED_TRAFFIC_BYTES = {"vgg": 756.6e6, "conv1": 307.4e6, "conv2": 313.1e6, "conv3": 107.9e6}
 
 
 def log(*a):
