@@ -140,6 +140,8 @@ def main():
     ap.add_argument("--no-layers", action="store_true", help="skip the per-layer table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true", help="skip the register-only MFMA ceiling")
+    ap.add_argument("--vgg16", action="store_true",
+                    help="time the nine distinct 3x3 shapes of a VGG-16 style network at minibatch 64")
     ap.add_argument("--minibatch", action="store_true",
                     help="time the headline layer's geometry at minibatch sizes 4 ... 256")
     ap.add_argument("--block-sizes", action="store_true",
@@ -447,6 +449,30 @@ def main():
                     log(f"[bench] table1 {name:18s} bprop-{kind}: {g['ms']:8.4f} ms {g['tflops']:7.2f} TFLOP/s "
                         f"{100 * g['frac_peak']:5.1f}% of peak")
         result["table1"] = rows
+
+    if args.vgg16:
+        # the nine distinct 3x3 shapes of a VGG-16 style network at minibatch 64; random data made on
+        # the device (the first layers' tensors are 0.8 GB each; timing does not depend on the values)
+        rows = {}
+        tot_ms, tot_fl = 0.0, 0.0
+        for name, Lv in W.VGG16.items():
+            d_in = torch.rand((Lv.Nc, Lv.Hi, Lv.Wi, Lv.Nb), device="cuda")
+            d_f = torch.randn((Lv.Nc, Lv.Sk, Lv.Sk, Lv.No), device="cuda") * 0.01
+            out = torch.empty((Lv.No, Lv.Hi, Lv.Wi, Lv.Nb), device="cuda")
+            ms, _ = time_layer(torch, B, Lv, d_in, d_f, out, 20, 3, None, min_warm_ms=WARM_MS_FLOOR)
+            fl = B.mdnn_conv_flops(Lv.Nb, Lv.Wi, Lv.Hi, Lv.Nc, Lv.No, Lv.Sk)
+            rows[name] = {"ms": round(ms, 4), "tflops": round(fl / ms / 1e9, 2),
+                          "frac_peak": round(fl / ms / 1e9 / PEAK_FP32_MATRIX_TFLOPS, 4),
+                          "variant": B.mdnn_choose_variant(Lv.Nb, Lv.Wi, Lv.Hi, Lv.Nc, Lv.No, Lv.Sk, Lv.stride, Lv.pad)}
+            tot_ms += ms
+            tot_fl += fl
+            log(f"[bench] vgg16 {name:8s} {Lv.Nc:4d}->{Lv.No:4d} @{Lv.Hi:3d}: {ms:8.4f} ms {fl / ms / 1e9:7.2f} TFLOP/s "
+                f"{100 * fl / ms / 1e9 / PEAK_FP32_MATRIX_TFLOPS:5.1f}%  variant={rows[name]['variant']}")
+            del d_in, d_f, out
+        rows["nine_shapes_once_each"] = {"ms": round(tot_ms, 3), "tflops": round(tot_fl / tot_ms / 1e9, 2),
+                                         "frac_peak": round(tot_fl / tot_ms / 1e9 / PEAK_FP32_MATRIX_TFLOPS, 4)}
+        log(f"[bench] vgg16 nine shapes once each: {tot_ms:.3f} ms, {tot_fl / tot_ms / 1e9:.1f} TFLOP/s")
+        result["vgg16"] = rows
 
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample ...")

@@ -73,6 +73,19 @@ for _i, (_name, _wi, _nc, _no, _sk, _st, _pad, _ce) in enumerate([
                            SEED_BASE + 50 + _i), _ce)
 
 
+# The nine distinct 3x3 convolution shapes of a VGG-16 style network at minibatch 64 (the `vgg`
+# benchmark layer is its 256 -> 256 layer at 56 x 56): a third workload, synthetic data only.
+VGG16 = {}
+for _i, (_name, _hw, _nc, _no) in enumerate([
+        ("conv1_1", 224,   3,  64), ("conv1_2", 224,  64,  64),
+        ("conv2_1", 112,  64, 128), ("conv2_2", 112, 128, 128),
+        ("conv3_1",  56, 128, 256), ("conv3_2",  56, 256, 256),
+        ("conv4_1",  28, 256, 512), ("conv4_2",  28, 512, 512),
+        ("conv5_1",  14, 512, 512)]):
+    VGG16[_name] = Layer("vgg16." + _name, 64, _hw, _hw, _nc, _no, 3, 1, 1, 1.0,
+                         "uniform01", "normal_0p01", SEED_BASE + 80 + _i)
+
+
 def custom(name, Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha=1.0,
            in_dist="uniform_pm1", filt_dist="uniform_pm1", seed=SEED_BASE + 1000) -> Layer:
     return Layer(name, Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha, in_dist, filt_dist, seed)

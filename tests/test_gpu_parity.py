@@ -129,6 +129,36 @@ def test_paper_table1_shapes_sampled(env, name):
     check(got[o, y, x, n], vals, absum, L.alpha, name)
 
 
+@pytest.mark.parametrize("name", list(W.VGG16))
+def test_vgg16_shapes_sampled(env, name):
+    """The nine distinct 3x3 shapes of a VGG-16 style network at minibatch 64, full size (tensors up
+    to 0.8 GB, 12544 tiles): 20 000 sampled outputs plus the corners against the oracle's
+    one-by-one evaluation, default variant -- the launch configuration `bench.py --vgg16` times."""
+    torch, B, oracle = env
+    L = W.VGG16[name]
+    say(f"[parity-vgg16] layer={name} seed={L.seed} plan="
+        f"{B.mdnn_describe_launch(L.Nb, L.Wi, L.Hi, L.Nc, L.No, L.Sk, L.stride, L.pad)}")
+    inp, filt = W.make_inputs(L)
+    d_in, d_f = torch.from_numpy(inp).cuda(), torch.from_numpy(filt).cuda()
+    out = B.mdnn_conv_fprop(d_in, d_f, L.stride, L.pad, L.alpha)
+    torch.cuda.synchronize()
+    No, Ho, Wo, Nb = out.shape
+    rng = np.random.default_rng(L.seed)
+    npts = 20000
+    idx = np.stack([rng.integers(0, No, npts), rng.integers(0, Ho, npts),
+                    rng.integers(0, Wo, npts), rng.integers(0, Nb, npts)], axis=1).astype(np.int32)
+    idx[0] = (0, 0, 0, 0)
+    idx[1] = (No - 1, Ho - 1, Wo - 1, Nb - 1)
+    idx[2] = (No - 1, 0, Wo - 1, 0)
+    idx[3] = (0, Ho - 1, 0, Nb - 1)
+    t = torch.from_numpy(idx.astype(np.int64)).cuda()
+    got = out[t[:, 0], t[:, 1], t[:, 2], t[:, 3]].cpu().numpy()        # gather on the device: out is up to 0.8 GB
+    assert bool(torch.isfinite(out).all())
+    del out, d_in, d_f
+    vals, absum = oracle.conv_fprop_points(inp, filt, idx, L.stride, L.pad, L.alpha)
+    check(got, vals, absum, L.alpha, name)
+
+
 # ------------------------------------------------------- odd shapes, all variants
 ODD = [
     # name              Nb  Hi  Wi  Nc  No  Sk st pad alpha
