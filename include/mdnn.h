@@ -133,6 +133,31 @@ mdnn_status mdnn_conv_bprop_data(const float* dout, const float* filt, float* di
                                  int Sk, int stride, int pad, float alpha, void* stream);
 
 /*
+ * mdnn_conv_bprop_data for callers that cannot allocate device memory or hand
+ * over a workspace: code that records a HIP graph, tight serving loops,
+ * harnesses that forbid allocation.  Same operation, same kernels, same result
+ * bit for bit; the workspace is a static device array of
+ * MDNN_STATIC_SCRATCH_BYTES inside the library (every GPU the library runs on
+ * holds its own copy until the process ends).  The call allocates and frees
+ * nothing and uses no memset.  A problem whose workspace
+ * (mdnn_conv_bprop_data_workspace()) exceeds MDNN_STATIC_SCRATCH_BYTES is
+ * refused with MDNN_ETOOBIG before anything is enqueued: the limit covers the
+ * rearranged bank of every stride-1 layer up to 1024 x 1024 filters of 3 x 3,
+ * and strided layers whose per-class results fit beside their bank.
+ * All calls on one GPU share that GPU's array, which keeps whatever the last
+ * call left in it (every call overwrites all it reads, nothing has to start
+ * at zero): calls that overlap in time on one GPU -- different streams, or two
+ * host threads -- race; calls on one stream are ordered and safe.  The first
+ * call on a GPU looks up the array's address there (a runtime query, no
+ * allocation); make that call outside a graph capture.  Other rules as for
+ * mdnn_conv_bprop_data.
+ */
+#define MDNN_STATIC_SCRATCH_BYTES (40u << 20)
+mdnn_status mdnn_conv_bprop_data_static(const float* dout, const float* filt, float* din,
+                                        int Nb, int Wi, int Hi, int Nc, int No,
+                                        int Sk, int stride, int pad, float alpha, void* stream);
+
+/*
  * Filter gradient (BPROP with respect to the weights), the other half of what
  * the paper leaves as a conjecture (abstract, Section 3.5).  It is the
  * per-coordinate patch x filter-matrix product of Section 3 turned round: the

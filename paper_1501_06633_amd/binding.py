@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
     L.mdnn_conv_bprop_data_workspace.restype = i
     L.mdnn_conv_bprop_data.argtypes = [p, p, p, p, ctypes.c_size_t, i, i, i, i, i, i, i, i, f, p]
     L.mdnn_conv_bprop_data.restype = i
+    L.mdnn_conv_bprop_data_static.argtypes = [p, p, p, i, i, i, i, i, i, i, i, f, p]
+    L.mdnn_conv_bprop_data_static.restype = i
     L.mdnn_conv_bprop_filter_workspace.argtypes = [i] * 8 + [ctypes.POINTER(ctypes.c_size_t)]
     L.mdnn_conv_bprop_filter_workspace.restype = i
     L.mdnn_conv_bprop_filter.argtypes = [p, p, p, p, ctypes.c_size_t, i, i, i, i, i, i, i, i, f, p]
@@ -225,6 +227,40 @@ def mdnn_conv_bprop_data(dout, filt, in_hw, stride, pad, alpha=1.0, din=None, wo
                                     float(alpha), stream.cuda_stream or None)
     if st != MDNN_OK:
         raise MdnnError(st, "mdnn_conv_bprop_data")
+    return din
+
+
+MDNN_STATIC_SCRATCH_BYTES = 40 << 20
+
+
+def mdnn_conv_bprop_data_static(dout, filt, in_hw, stride, pad, alpha, din, stream=None):
+    """mdnn_conv_bprop_data over the library's static device array instead of a workspace: the
+    caller passes the result tensor ``din`` (Nc,Hi,Wi,Nb) too, so nothing is allocated anywhere."""
+    import torch
+
+    if not (dout.is_cuda and filt.is_cuda and din.is_cuda):
+        raise ValueError("mdnn_conv_bprop_data_static needs device tensors (no CPU path exists)")
+    if dout.dtype != torch.float32 or filt.dtype != torch.float32 or din.dtype != torch.float32:
+        raise ValueError("fp32 only")
+    if not (dout.is_contiguous() and filt.is_contiguous() and din.is_contiguous()):
+        raise ValueError("tensors must be contiguous")
+    No, Ho, Wo, Nb = dout.shape
+    Nc, Sk, Sk2, No2 = filt.shape
+    Hi, Wi = in_hw
+    if No2 != No or Sk2 != Sk or tuple(din.shape) != (Nc, Hi, Wi, Nb):
+        raise ValueError("tensor shapes do not match")
+    st, wo, ho = mdnn_out_dims(Wi, Hi, Sk, stride, pad)
+    if st != MDNN_OK:
+        raise MdnnError(st, "mdnn_out_dims")
+    if (wo, ho) != (Wo, Ho):
+        raise ValueError("dout spatial size does not match the forward geometry")
+    if stream is None:
+        stream = torch.cuda.current_stream(dout.device)
+    st = lib().mdnn_conv_bprop_data_static(dout.data_ptr(), filt.data_ptr(), din.data_ptr(),
+                                           Nb, Wi, Hi, Nc, No, Sk, stride, pad, float(alpha),
+                                           stream.cuda_stream or None)
+    if st != MDNN_OK:
+        raise MdnnError(st, "mdnn_conv_bprop_data_static")
     return din
 
 

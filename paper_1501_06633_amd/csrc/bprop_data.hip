@@ -19,10 +19,22 @@
 // convolution with s*s*Nc filters, and a gather interleaves the classes into din.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "mdnn_internal.h"
 
 namespace mdnn {
 namespace {
+
+// Workspace of the allocation-free data-gradient entry point: the rearranged filter bank (and,
+// for stride > 1, the per-class results) of one call.  One copy per GPU, held from the moment
+// the library's code is loaded there until the process ends.  In host code this name is only a
+// handle for hipGetSymbolAddress(); the device address it yields is what kernels are given.
+constexpr size_t kStaticScratchBytes = MDNN_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex scratch_lock;
+void*      scratch_addr[kMaxDevices];      // device address of `scratch` on each GPU, once looked up
 
 // F'[(o*SkSk + t')*Nc + c] = filt[(c*SkSk + SkSk-1-t')*No + o]: per tap a No x Nc
 // transpose, through a padded LDS tile so that both sides are coalesced.
@@ -104,6 +116,24 @@ __global__ void __launch_bounds__(256) gather_classes(const float* __restrict__ 
 }
 
 }  // namespace
+
+int static_scratch(void** ptr)
+{
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return (int)err;
+    if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(scratch_lock);
+    if (!scratch_addr[dev]) {
+        // each GPU has its own copy of the array at its own address: look it up with that GPU current
+        void* p = nullptr;
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess) return (int)err;
+        scratch_addr[dev] = p;
+    }
+    *ptr = scratch_addr[dev];
+    return 0;
+}
 
 int launch_flip_transpose(const float* filt, float* ft, int Nc, int No, int SkSk, void* stream)
 {

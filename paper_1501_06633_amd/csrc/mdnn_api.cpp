@@ -440,6 +440,37 @@ mdnn_status filter_grad_plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int
     return MDNN_OK;
 }
 
+// The kernels of one data-gradient call, enqueued on `stream`; every argument has been checked.
+mdnn_status bprop_data_enqueue(const BpropPlan& b, const float* dout, const float* filt, float* din, void* workspace,
+                               int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int pad,
+                               float alpha, void* stream)
+{
+    Geometry g;
+    check_geometry(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &g);       // succeeded inside bprop_plan
+    float* bank = static_cast<float*>(workspace);
+    float* e    = reinterpret_cast<float*>(static_cast<char*>(workspace) + b.e_offset);
+
+    // the transposed problem: No input channels of Ho x Wo, b.filters_t filters of T x T, stride 1
+    mdnn::ConvParams p;
+    int v = -1;
+    const mdnn_status ps = plan(Nb, g.Wo, g.Ho, No, b.filters_t, b.T, 1, b.pad_t, nullptr, &p, &v);
+    if (ps != MDNN_OK) return ps;
+    if (p.Ho != b.He || p.Wo != b.We) return MDNN_EINVAL;          // cannot happen: Ho + 2 pad_t - T + 1 == He
+
+    if (stride == 1) {
+        if (mdnn::launch_flip_transpose(filt, bank, Nc, No, Sk * Sk, stream) != 0) return MDNN_ELAUNCH;
+        p.in = dout;  p.filt = bank;  p.out = din;
+        p.alpha = alpha;
+        return mdnn::launch_variant(v, p, stream) == 0 ? MDNN_OK : MDNN_ELAUNCH;
+    }
+    if (mdnn::launch_class_filters(filt, bank, Nc, No, Sk, stride, b.T, stream) != 0) return MDNN_ELAUNCH;
+    p.in = dout;  p.filt = bank;  p.out = e;
+    p.alpha = alpha;
+    if (mdnn::launch_variant(v, p, stream) != 0) return MDNN_ELAUNCH;
+    return mdnn::launch_gather_classes(e, din, Nc, Hi, Wi, Nb, b.He, b.We, stride, pad, stream) == 0
+               ? MDNN_OK : MDNN_ELAUNCH;
+}
+
 }  // namespace
 
 mdnn_status mdnn_conv_bprop_filter_workspace(int Nb, int Wi, int Hi, int Nc, int No,
@@ -490,31 +521,23 @@ mdnn_status mdnn_conv_bprop_data(const float* dout, const float* filt, float* di
     if (!std::isfinite(alpha)) return MDNN_EINVAL;
     if (workspace_bytes < b.total_bytes) return MDNN_EINVAL;
     if (((uintptr_t)dout | (uintptr_t)filt | (uintptr_t)din | (uintptr_t)workspace) & 15u) return MDNN_EALIGN;
+    return bprop_data_enqueue(b, dout, filt, din, workspace, Nb, Wi, Hi, Nc, No, Sk, stride, pad, alpha, stream);
+}
 
-    Geometry g;
-    check_geometry(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &g);       // succeeded inside bprop_plan
-    float* bank = static_cast<float*>(workspace);
-    float* e    = reinterpret_cast<float*>(static_cast<char*>(workspace) + b.e_offset);
-
-    // the transposed problem: No input channels of Ho x Wo, b.filters_t filters of T x T, stride 1
-    mdnn::ConvParams p;
-    int v = -1;
-    const mdnn_status ps = plan(Nb, g.Wo, g.Ho, No, b.filters_t, b.T, 1, b.pad_t, nullptr, &p, &v);
-    if (ps != MDNN_OK) return ps;
-    if (p.Ho != b.He || p.Wo != b.We) return MDNN_EINVAL;          // cannot happen: Ho + 2 pad_t - T + 1 == He
-
-    if (stride == 1) {
-        if (mdnn::launch_flip_transpose(filt, bank, Nc, No, Sk * Sk, stream) != 0) return MDNN_ELAUNCH;
-        p.in = dout;  p.filt = bank;  p.out = din;
-        p.alpha = alpha;
-        return mdnn::launch_variant(v, p, stream) == 0 ? MDNN_OK : MDNN_ELAUNCH;
-    }
-    if (mdnn::launch_class_filters(filt, bank, Nc, No, Sk, stride, b.T, stream) != 0) return MDNN_ELAUNCH;
-    p.in = dout;  p.filt = bank;  p.out = e;
-    p.alpha = alpha;
-    if (mdnn::launch_variant(v, p, stream) != 0) return MDNN_ELAUNCH;
-    return mdnn::launch_gather_classes(e, din, Nc, Hi, Wi, Nb, b.He, b.We, stride, pad, stream) == 0
-               ? MDNN_OK : MDNN_ELAUNCH;
+mdnn_status mdnn_conv_bprop_data_static(const float* dout, const float* filt, float* din,
+                                        int Nb, int Wi, int Hi, int Nc, int No,
+                                        int Sk, int stride, int pad, float alpha, void* stream)
+{
+    if (!dout || !filt || !din) return MDNN_ENULL;
+    BpropPlan b;
+    const mdnn_status bs = bprop_plan(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &b);
+    if (bs != MDNN_OK) return bs;
+    if (!std::isfinite(alpha)) return MDNN_EINVAL;
+    if (b.total_bytes > (size_t)MDNN_STATIC_SCRATCH_BYTES) return MDNN_ETOOBIG;
+    if (((uintptr_t)dout | (uintptr_t)filt | (uintptr_t)din) & 15u) return MDNN_EALIGN;
+    void* scratch = nullptr;
+    if (mdnn::static_scratch(&scratch) != 0 || !scratch) return MDNN_ELAUNCH;
+    return bprop_data_enqueue(b, dout, filt, din, scratch, Nb, Wi, Hi, Nc, No, Sk, stride, pad, alpha, stream);
 }
 
 mdnn_status mdnn_mfma_peak_probe(float* sink, int blocks, int waves_per_block, int iters,

@@ -83,6 +83,10 @@ int launch_class_filters(const float* filt, float* fc, int Nc, int No, int Sk, i
 int launch_gather_classes(const float* e, float* din, int Nc, int Hi, int Wi, int Nb, int He, int We,
                           int stride, int pad, void* stream);
 
+// Device address, on the current GPU, of the static array of MDNN_STATIC_SCRATCH_BYTES bytes behind
+// mdnn_conv_bprop_data_static (bprop_data.hip); looked up once per GPU.  Returns 0 or a HIP error code.
+int static_scratch(void** ptr);
+
 // Filter gradient (bprop_filter.hip): everything a workgroup needs.
 struct FilterGradParams {
     const float* in;

@@ -34,7 +34,7 @@ def test_exports_every_declared_symbol(L):
     assert {"mdnn_conv_fprop", "mdnn_conv_fprop_variant", "mdnn_out_dims", "mdnn_conv_flops",
             "mdnn_status_string", "mdnn_variant_count", "mdnn_variant_name",
             "mdnn_choose_variant", "mdnn_describe_launch", "mdnn_mfma_peak_probe",
-            "mdnn_conv_bprop_data", "mdnn_conv_bprop_data_workspace",
+            "mdnn_conv_bprop_data", "mdnn_conv_bprop_data_workspace", "mdnn_conv_bprop_data_static",
             "mdnn_conv_bprop_filter", "mdnn_conv_bprop_filter_workspace", "mdnn_sgemm_tn"} <= set(names)
     for n in names:
         assert hasattr(L, n), f"libmdnn.so does not export {n}"
@@ -192,6 +192,29 @@ def test_bprop_data_workspace_and_argument_checks(L):
     assert call_b(wb=need - 1) == B.MDNN_EINVAL
     assert call_b(a=float("nan")) == B.MDNN_EINVAL
     assert call_b(w=FAKE + 4) == B.MDNN_EALIGN
+
+
+def test_static_data_gradient_argument_checks(L):
+    """The allocation-free variant refuses everything the workspace call refuses, and whatever does
+    not fit its static array, before it touches the GPU."""
+    args = (8, 8, 8, 2, 4, 3, 1, 1)
+    call_s = lambda d=FAKE, f=FAKE, o=FAKE, a=1.0, dims=args: L.mdnn_conv_bprop_data_static(d, f, o, *dims, a, None)
+    assert call_s(d=None) == B.MDNN_ENULL and call_s(f=None) == B.MDNN_ENULL and call_s(o=None) == B.MDNN_ENULL
+    assert call_s(a=float("nan")) == B.MDNN_EINVAL
+    assert call_s(o=FAKE + 4) == B.MDNN_EALIGN
+    assert call_s(dims=(8, 8, 8, 2, 4, 3, 1, 3)) == B.MDNN_EINVAL          # stride 1 with pad > Sk - 1
+    assert call_s(dims=(8, 2, 2, 2, 4, 3, 1, 0)) == B.MDNN_EINVAL          # no output
+    # the limit is the header's constant, in terms of mdnn_conv_bprop_data_workspace()
+    header = open(HEADER).read()
+    m = re.search(r"#define\s+MDNN_STATIC_SCRATCH_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", header)
+    assert m and (int(m.group(1)) << int(m.group(2))) == B.MDNN_STATIC_SCRATCH_BYTES
+    fits = (128, 12, 12, 1024, 1024, 3, 1, 1)        # bank of 36 MiB
+    assert B.mdnn_conv_bprop_data_workspace(*fits)[1] <= B.MDNN_STATIC_SCRATCH_BYTES
+    assert call_s(dims=fits, o=FAKE + 4) == B.MDNN_EALIGN                   # passed the size check
+    for too_big in [(128, 227, 227, 3, 96, 11, 4, 0),                       # per-class results of 80 MB
+                    (128, 12, 12, 1024, 1280, 3, 1, 1)]:                    # bank of 45 MiB
+        assert B.mdnn_conv_bprop_data_workspace(*too_big)[1] > B.MDNN_STATIC_SCRATCH_BYTES
+        assert call_s(dims=too_big) == B.MDNN_ETOOBIG
 
 
 def test_bprop_filter_workspace_and_argument_checks(L):
