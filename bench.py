@@ -31,9 +31,29 @@ WARM_MS_FLOOR = 100.0
 # HBM-side bytes per launch (fetched + written), measured with rocprofv3 --pmc FETCH_SIZE and
 # --pmc WRITE_SIZE (one counter per run) on this kernel and scaled by what the same counters read
 # for a plain 256 MiB device copy in the same run (--copy-calibration): factor 2.000 for
-# FETCH_SIZE, 1.000 for WRITE_SIZE.  Not measurable from inside this script; the summary with the
-# commands is profiles/conv_fprop_hbm_traffic_pmc.txt.
-MEASURED_TRAFFIC_BYTES = {"vgg": 756.6e6, "conv1": 307.4e6, "conv2": 313.1e6, "conv3": 107.9e6}
+# FETCH_SIZE, 1.000 for WRITE_SIZE.  Not measurable from inside this script: each figure is recorded
+# together with the launch plan it was taken with (the summary with the commands is SOURCE), and is
+# reported only when the plan launched now is that plan; otherwise `traffic` is null.
+TRAFFIC_SOURCE = "profiles/conv_fprop_hbm_traffic_pmc.txt"
+PLAN_KEYS = ("variant", "tiles", "whole", "halved", "thirded", "quartered", "pieces_first", "table_entries")
+RECORDED_TRAFFIC = {
+    "vgg":   {"bytes": 756.6e6, "plan": {"variant": "o128m128k8", "tiles": 3136, "whole": 3072, "halved": 0, "thirded": 0,
+                                         "quartered": 64, "pieces_first": 256, "table_entries": 2304}},
+    "conv1": {"bytes": 307.4e6, "plan": {"variant": "o96m256", "tiles": 1513, "whole": 1513, "halved": 0, "thirded": 0,
+                                         "quartered": 0, "pieces_first": 0, "table_entries": 368}},
+    "conv2": {"bytes": 313.1e6, "plan": {"variant": "o128m128k8", "tiles": 1458, "whole": 1280, "halved": 0, "thirded": 0,
+                                         "quartered": 178, "pieces_first": 256, "table_entries": 2400}},
+    "conv3": {"bytes": 107.9e6, "plan": {"variant": "o128m128", "tiles": 507, "whole": 507, "halved": 0, "thirded": 0,
+                                         "quartered": 0, "pieces_first": 0, "table_entries": 2304}},
+}
+
+
+def recorded_traffic(workload, plan):
+    """The recorded HBM bytes per launch if the launch plan is the one they were measured with, else None."""
+    rec = RECORDED_TRAFFIC.get(workload)
+    if rec is None or any(plan.get(k) != rec["plan"][k] for k in PLAN_KEYS):
+        return None
+    return rec["bytes"]
 
 
 def log(*a):
@@ -88,9 +108,35 @@ def layer_report(torch, B, W, name, steps, warmup, variant=None, min_warm_ms=0.0
     return rep, (L, inp, filt, out)
 
 
+def parity(B, W, L, inp, filt, out, variant=None):
+    """Untimed check of a buffer the timed launches wrote: at least two outputs in every 16-row by
+    half-tile-wide block of the launch grid (so in every tile and in every piece a tile may have
+    been cut into), first and last element of each block among them, against the oracle's
+    one-by-one evaluation.  Returns max |gpu - oracle| / (|alpha| * sum |x w|) and the count."""
+    import numpy as np
+    import oracle
+
+    plan = B.mdnn_describe_launch(L.Nb, L.Wi, L.Hi, L.Nc, L.No, L.Sk, L.stride, L.pad, variant)
+    to, tm = map(int, plan["tile"].split("x"))
+    No, Ho, Wo, Nb = out.shape
+    idx = W.output_points((No, Nb), Ho, Wo, min(16, to), max(tm // 2, 4), 2, L.seed % 1000)
+    want, absum = oracle.conv_fprop_points(inp, filt, idx, L.stride, L.pad, L.alpha)
+    import torch
+    t = torch.from_numpy(idx.astype(np.int64)).to(out.device)
+    got = out[t[:, 0], t[:, 1], t[:, 2], t[:, 3]].cpu().numpy()
+    err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    scale = abs(L.alpha) * absum
+    zero = scale == 0
+    ratio = np.zeros_like(err)
+    np.divide(err, scale, out=ratio, where=~zero)
+    ok = bool(np.isfinite(got).all() and (got[zero] == 0).all() and float(ratio.max()) <= 1e-4)
+    return {"max_err_over_A": float(ratio.max()), "points": int(idx.shape[0]), "bound": 1e-4, "ok": ok,
+            "sampling": f"2 per {min(16, to)}x{max(tm // 2, 4)} block of the No x M output, block corners included"}
+
+
 def cpu_baseline(W, name):
-    """The oracle as it stands, on a bounded sample: the first `No_s` filters of
-    the layer (all positions, whole batch), sized for roughly 10 s of CPU work."""
+    """The oracle as it stands on the whole layer, one pass (all output filters, all positions,
+    whole batch): a few seconds on 16 host cores, about 15 s on 8."""
     import numpy as np
     import oracle
 
@@ -140,6 +186,8 @@ def main():
     ap.add_argument("--no-layers", action="store_true", help="skip the per-layer table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true", help="skip the register-only MFMA ceiling")
+    ap.add_argument("--no-parity", action="store_true",
+                    help="skip the check of the timed output buffers against the oracle (stratified points)")
     ap.add_argument("--vgg16", action="store_true",
                     help="time the nine distinct 3x3 shapes of a VGG-16 style network at minibatch 64")
     ap.add_argument("--minibatch", action="store_true",
@@ -206,13 +254,25 @@ def main():
                    "layout": "in CHWN, filt (C,Sk,Sk,No), out (No,Ho,Wo,Nb)"},
         "roofline": {"bound": "mfma", "achieved": rep["tflops"], "peak": PEAK_FP32_MATRIX_TFLOPS,
                      "unit": "TFLOP/s", "frac": rep["frac_peak"],
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if args.variant is None else None,
-                     "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, copy-calibrated)",
+                     "traffic": None, "traffic_source": TRAFFIC_SOURCE,
+                     "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, copy-calibrated), recorded "
+                                     "with the launch plan it was measured on; null when the plan differs",
                      "algorithmic_bytes": rep["compulsory_bytes"]},
         "frac_of_fp32_matrix_peak": rep["frac_peak"],
+        "max_err_over_A": None,
         "paper_context": {"best_computational_efficiency": 0.963, "machine": "NVIDIA GTX 980 (Maxwell), Table 1",
                           "note": "another machine and another peak: context, not the target"},
     }
+
+    result["roofline"]["traffic"] = recorded_traffic(args.workload, result["config"]["plan"])
+    if not args.no_parity:
+        # the buffer the timed launches wrote, checked after the clock has stopped
+        _, inp_h, filt_h, out_h = ctx
+        result["parity"] = parity(B, W, L, inp_h, filt_h, out_h, args.variant)
+        result["max_err_over_A"] = result["parity"]["max_err_over_A"]
+        log(f"[bench] parity of the timed buffer: {result['parity']}")
+        if not result["parity"]["ok"]:
+            sys.exit(f"bench.py: the timed output of {args.workload} does not match the oracle: {result['parity']}")
 
     if args.copy_calibration:
         src = torch.rand(64 * 1024 * 1024, device="cuda")          # 256 MiB read, 256 MiB written
@@ -269,11 +329,20 @@ def main():
                 layers[name] = rep
                 continue
             steps = {"tiny": 200, "conv1": 50, "conv2": 50, "conv3": 100, "vgg": 30}[name]
-            r, _ = layer_report(torch, B, W, name, steps, 5, min_warm_ms=WARM_MS_FLOOR)
+            r, lctx = layer_report(torch, B, W, name, steps, 5, min_warm_ms=WARM_MS_FLOOR)
+            if not args.no_parity:
+                pr = parity(B, W, *lctx)
+                r["max_err_over_A"], r["parity_points"] = pr["max_err_over_A"], pr["points"]
+                if not pr["ok"]:
+                    sys.exit(f"bench.py: the timed output of {name} does not match the oracle: {pr}")
             layers[name] = r
             log(f"[bench] {name}: {r['ms']} ms, {r['tflops']} TFLOP/s ({100 * r['frac_peak']:.1f}%) "
                 f"variant={r['variant']}")
-        result["layers"] = {k: {kk: v[kk] for kk in ("variant", "ms", "tflops", "frac_peak", "compulsory_GBps")}
+        if not args.no_parity and args.workload in layers and "parity" in result:
+            layers[args.workload]["max_err_over_A"] = result["parity"]["max_err_over_A"]
+            layers[args.workload]["parity_points"] = result["parity"]["points"]
+        result["layers"] = {k: {kk: v[kk] for kk in ("variant", "ms", "tflops", "frac_peak", "compulsory_GBps",
+                                                     "max_err_over_A", "parity_points") if kk in v}
                             for k, v in layers.items()}
 
     if args.block_sizes:

@@ -28,9 +28,9 @@ typedef enum mdnn_status {
                            non-finite alpha, unknown variant name */
     MDNN_ENULL   = 2,   /* a required pointer is NULL */
     MDNN_EALIGN  = 3,   /* a tensor pointer is not 16-byte aligned */
-    MDNN_ETOOBIG = 4,   /* in or out is 2^32 bytes or larger, or filt 2^31 bytes or larger (32-bit byte
-                           offsets are used on the device, the same kind of limit Section 3.1 notes
-                           for texture indices) */
+    MDNN_ETOOBIG = 4,   /* in or out is 2^32 bytes or larger, or filt 2^31 bytes or larger, or
+                           (Nc Sk^2 + 64) No floats reach 2^32 bytes (32-bit byte offsets are used on
+                           the device, the same kind of limit Section 3.1 notes for texture indices) */
     MDNN_ELAUNCH = 5    /* the HIP runtime refused the launch (hipGetLastError() != hipSuccess) */
 } mdnn_status;
 
@@ -71,7 +71,11 @@ mdnn_status mdnn_conv_fprop(const float* in, const float* filt, float* out,
  * Same operation with the tile variant chosen by the caller instead of the
  * built-in heuristic (for tests and tuning).  `variant` is one of the names
  * mdnn_variant_name() enumerates, or NULL / "" / "auto" for the heuristic.
- * Every variant computes the same function for every valid argument set.
+ * A name may be followed by ':' and one letter that pins how tiles are cut into
+ * the smaller blocks of Section 3.4: w = no tile is cut; h, t, q = the tiles of
+ * the last partial round in halves, thirds (48 + 48 + 32 filter rows), quarters;
+ * H, T, Q = every tile so.  A cut the kernel does not have is MDNN_EINVAL.
+ * Every variant and cut computes the same function for every valid argument set.
  */
 mdnn_status mdnn_conv_fprop_variant(const float* in, const float* filt, float* out,
                                     int Nb, int Wi, int Hi, int Nc, int No,
@@ -113,8 +117,9 @@ const char* mdnn_choose_variant(int Nb, int Wi, int Hi, int Nc, int No,
  *                       dout[o][y][x][n] * filt[c][ky][kx][o]
  *   (iy = y*stride - pad + ky, ix likewise); input pixels no window reaches get 0.
  *
- * The dimension arguments are those of the FORWARD call.  pad <= Sk - 1 is
- * required.  `workspace` is device memory of at least the size
+ * The dimension arguments are those of the FORWARD call; any pad the forward
+ * call accepts is accepted (a stride-1 layer with pad > Sk - 1 takes the same
+ * route as a strided one).  `workspace` is device memory of at least the size
  * mdnn_conv_bprop_data_workspace() reports (16-byte aligned); it receives the
  * rearranged filter bank and, for stride > 1, the per-residue-class results
  * that a last kernel interleaves into din (input pixels are split by
@@ -191,7 +196,7 @@ mdnn_status mdnn_conv_bprop_filter(const float* in, const float* dout, float* df
 
 /*
  * Plain SGEMM in the convolution's operand layout: the yardstick the paper's
- * conclusion (Section 4) holds its kernel against, and what Section 3's
+ * conclusion (Section 3.5) holds its kernel against, and what Section 3's
  * patch-times-filter-matrix product becomes for a 1 x 1 filter, where the patch
  * is the input itself.  It runs the FPROP kernel on that degenerate geometry
  * (one pixel, M images), so the inner loop is the convolution's own.

@@ -43,10 +43,15 @@ __global__ void __launch_bounds__(256) flip_transpose_filters(const float* __res
                                                               int Nc, int No, int SkSk)
 {
     __shared__ float tile[32][33];
-    const int tap = blockIdx.z;                 // destination tap t'
-    const int src_tap = SkSk - 1 - tap;
-    const int c0 = blockIdx.y * 32, o0 = blockIdx.x * 32;
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
+    // blockIdx.x walks the 32 x 32 blocks of the No x Nc matrix of every tap (grids are limited to
+    // 65535 in y and z, which a large filter's tap count or channel count could exceed)
+    const int o_blocks = (No + 31) / 32, c_blocks = (Nc + 31) / 32;
+    const int per_tap = o_blocks * c_blocks;
+    const int tap = (int)(blockIdx.x / (unsigned)per_tap);      // destination tap t'
+    const int rem = (int)(blockIdx.x - (unsigned)tap * (unsigned)per_tap);
+    const int src_tap = SkSk - 1 - tap;
+    const int c0 = (rem / o_blocks) * 32, o0 = (rem % o_blocks) * 32;
 #pragma unroll
     for (int j = 0; j < 32; j += 8) {
         const int c = c0 + ty + j, o = o0 + tx;
@@ -137,7 +142,8 @@ int static_scratch(void** ptr)
 
 int launch_flip_transpose(const float* filt, float* ft, int Nc, int No, int SkSk, void* stream)
 {
-    const dim3 grid((unsigned)((No + 31) / 32), (unsigned)((Nc + 31) / 32), (unsigned)SkSk);
+    // one workgroup per 32 x 32 block and tap: the bank holds fewer than 2^29 floats, so fewer than 2^31 blocks
+    const dim3 grid((unsigned)((size_t)((No + 31) / 32) * ((Nc + 31) / 32) * SkSk));
     hipLaunchKernelGGL(flip_transpose_filters, grid, dim3(256), 0, static_cast<hipStream_t>(stream),
                        filt, ft, Nc, No, SkSk);
     return (int)hipGetLastError();

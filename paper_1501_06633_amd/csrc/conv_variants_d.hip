@@ -1,0 +1,28 @@
+// Tile shapes of the FPROP convolution kernel, group d: the 96 x 256 tile with its halves, and the deep 64 x 256 tile.
+// Columns of a shape: waves along filters x along columns, matrix blocks per wave along filters x
+// along columns, slab depth, ring stages, floats per copy, barrier k-step, block edge.
+// An entry: name, workgroups that fit one compute unit, measured fraction of the matrix rate with
+// many tiles per unit / with few, offset-table entries kept in LDS (sized so that a long K does
+// not cost a resident workgroup).
+#include "conv_tile.h"
+
+namespace mdnn {
+namespace {
+
+typedef Cfg<1, 4, 3, 2, 16, 3, 4> C_o96m256;
+typedef Cfg<1, 4, 2, 2, 16, 3, 4> C_o64m256;
+
+const VariantEntry kGroup[] = {
+    make_entry<C_o96m256, 2>("o96m256", 2, 0.860f, 0.80f, 1536),
+    make_entry<C_o64m256>("o64m256", 2, 0.885f, 0.86f, 2304),
+};
+
+}  // namespace
+
+const VariantEntry* conv_variants_d(int* count)
+{
+    *count = (int)(sizeof(kGroup) / sizeof(kGroup[0]));
+    return kGroup;
+}
+
+}  // namespace mdnn

@@ -13,6 +13,7 @@ namespace {
 constexpr int     kComputeUnits = 256;          // MI355X
 constexpr int     kStripRows = 8;               // image rows per strip of the 2-D tile order
 constexpr int64_t kFourGiB = (int64_t)1 << 32;
+constexpr int     kMaxSlab = 64;                // no tile variant stages more rows of k than this at once
 
 struct Geometry {
     int     Wo, Ho;
@@ -45,6 +46,9 @@ mdnn_status check_geometry(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int s
     // wrap back into the buffer: keep the filter bank under 2 GiB.
     if (g->in_bytes >= kFourGiB || g->filt_bytes >= kFourGiB / 2 || g->out_bytes >= kFourGiB)
         return MDNN_ETOOBIG;
+    // Rows k >= K of the filter matrix read as zero because their byte offset lies beyond the end
+    // of the buffer; that needs the offsets of up to kMaxSlab rows past the last one to stay below 2^32.
+    if (((int64_t)Nc * Sk * Sk + kMaxSlab) * (int64_t)No * 4 >= kFourGiB) return MDNN_ETOOBIG;
     g->Wo = (int)Wo;
     g->Ho = (int)Ho;
     g->K  = (int64_t)Nc * Sk * Sk;
@@ -75,25 +79,63 @@ bool variant_usable(const mdnn::VariantInfo& v, int Nb, int No)
 
 // Tail balancing.  With T tiles on 256 compute units the last T mod 256 tiles form
 // a partial round that keeps a few units busy for a whole tile time.  Cutting
-// each of them into 2 or 4 pieces (less efficient, but short) can end the launch
-// sooner: the partial round then costs ceil(r*f/256)/f tile times, divided by the
-// pieces' relative efficiency.
-// Returns the cost of the partial round in tile times (0 if there is none).
-double choose_split(const mdnn::VariantInfo& v, int n_tiles, int* n_whole, int* split)
+// them into pieces (less efficient, but short) can end the launch sooner.  The
+// cuts a kernel may offer: halves and quarters of a tile, and for 128-row tiles
+// "thirds" of 48 + 48 + 32 filter rows.
+// What was measured: workgroups that share a unit advance through the contraction
+// at the same rate (the matrix pipe alternates between their waves), so a piece
+// that starts beside a whole tile ends with it, whatever its height, and the two
+// together take (128 + piece rows) / 128 tile times.  A second piece in the same
+// slot starts when the unit is nearly empty and runs alone, at about half the
+// matrix rate.  So the cut to take is the finest one that still leaves at most
+// one piece per unit:
+//   r <= 64 left-over tiles: quarters (1.25 tile times for the round instead of 2);
+//   r <= 85: thirds (1.375; 338 tiles of 128 x 128 on a 13 x 13 layer: 80 -> 86 % of peak);
+//   r <= 128: halves (1.5);
+//   r <= 192: quarters in chains of up to three (a mixture that gives every unit a half or
+//       a third plus a quarter has fewer rows on the busiest unit, but its second pieces run
+//       alone: 533 us against 488 us on a 14 x 14 layer with 392 tiles);
+// each weighed by the piece's relative efficiency and taken only if it beats the coarser
+// choice by a margin.
+struct Cut {
+    int    n_whole, n_half, n_third, n_quarter;
+    double cost;                       // of the partial round, in tile times (0 if there is none)
+    int    pieces() const { return 2 * n_half + 3 * n_third + 4 * n_quarter; }
+};
+
+// `force`: 0 = choose; 'w' = no cutting; 'h', 't', 'q' = the left-over tiles in halves, thirds, quarters;
+// 'H', 'T', 'Q' = every tile so (tests and the block-size experiment pin a cut this way).  A kernel
+// that lacks the cut asked for returns n_whole = -1.
+Cut choose_cut(const mdnn::VariantInfo& v, int n_tiles, char force = 0)
 {
-    *n_whole = n_tiles;
-    *split = 1;
-    const int r = n_tiles % kComputeUnits;
-    if (r == 0) return 0.0;
-    if (v.max_split < 2) return 1.0;
-    static const double rel_eff[5] = {0, 1.0, 0.93, 0, 0.85};
-    double best = 1.0;
-    for (int f = 2; f <= v.max_split; f *= 2) {
-        const double rounds = (double)((r * f + kComputeUnits - 1) / kComputeUnits) / f / rel_eff[f];
-        if (rounds < best - 0.05) { best = rounds; *split = f; }
+    Cut c = {n_tiles, 0, 0, 0, 0.0};
+    if (force) {
+        const bool all = force == 'H' || force == 'T' || force == 'Q';
+        const int  n = all ? n_tiles : n_tiles % kComputeUnits;
+        const char f = all ? (char)(force - 'A' + 'a') : force;
+        const bool has = f == 'w' || (f == 'h' && v.max_split >= 2) || (f == 't' && v.thirds) || (f == 'q' && v.max_split >= 4);
+        if (!has) { c.n_whole = -1; return c; }
+        if (f == 'h') c.n_half = n;
+        if (f == 't') c.n_third = n;
+        if (f == 'q') c.n_quarter = n;
+        c.n_whole = n_tiles - (f == 'w' ? 0 : n);
+        c.cost = n ? 1.0 : 0.0;
+        return c;
     }
-    if (*split > 1) *n_whole = n_tiles - r;
-    return best;
+    const int r = n_tiles % kComputeUnits;
+    if (r == 0) return c;
+    c.cost = 1.0;
+    if (v.max_split < 2) return c;
+    const double e2 = 0.93, e3 = 0.90, e4 = 0.85;      // a half, a 48-row third, a quarter against a whole tile
+    auto rounds_of = [&](int f) { return (double)((r * f + kComputeUnits - 1) / kComputeUnits) / f; };
+    auto take = [&](double cost, int nh, int nt, int nq) {
+        if (cost < c.cost - 0.05) { c.cost = cost;  c.n_half = nh;  c.n_third = nt;  c.n_quarter = nq; }
+    };
+    take(rounds_of(2) / e2, r, 0, 0);
+    if (v.thirds && 3 * r <= kComputeUnits) take(0.375 / e3, 0, r, 0);
+    if (v.max_split >= 4) take(rounds_of(4) / e4, 0, 0, r);
+    if (c.pieces() > 0) c.n_whole = n_tiles - r;
+    return c;
 }
 
 // Cost of a variant: tiles are dealt to 256 compute units, a unit works through
@@ -101,14 +143,14 @@ double choose_split(const mdnn::VariantInfo& v, int n_tiles, int* n_whole, int* 
 // matrix pipe, they do not add to it), and a tile costs its full area even
 // when it hangs over the edge of the output matrix (Section 3.3's point about
 // credit for unnecessary work).  The last, partial round costs what
-// choose_split() makes of it.
+// choose_cut() makes of it.
 double variant_cost(const mdnn::VariantInfo& v, int No, int64_t M)
 {
     const int64_t tiles = (int64_t)div_up(No, v.tile_o) * div_up(M, v.tile_m);
     if (tiles > ((int64_t)1 << 26)) return 1e300;
-    int n_whole, split;
-    const double tail = choose_split(v, (int)tiles, &n_whole, &split);
-    const double rounds = (double)(tiles / kComputeUnits) + tail;
+    const Cut cut = choose_cut(v, (int)tiles);
+    const int n_whole = cut.n_whole;
+    const double rounds = (double)(tiles / kComputeUnits) + cut.cost;
     // Which of the two measured efficiencies applies.  Tiles that hold two workgroups per unit: "few"
     // means fewer than 4 7/8 rounds.  Tiles that hold three or more: more than two rounds count as
     // many.  Exception for three per unit: when the whole tiles fill the 768 slots once and a part
@@ -117,7 +159,7 @@ double variant_cost(const mdnn::VariantInfo& v, int No, int64_t M)
     // idle.  128x128: 73-82 % at 992 ... 1120 tiles against 93 % at 768, at 1088 with 256 pieces in
     // front, and from 1248 on; 96x128: 91 % at 768 tiles, 74 % at 1024.  (The small tiles at four
     // and more per unit show no such dip: 32x128 follows plain rounds of 256.)
-    const int64_t n_pieces = (tiles - n_whole) * split;
+    const int64_t n_pieces = cut.pieces();
     double eff;
     if (v.est_wg_per_cu >= 3) {
         const int64_t slots = 3 * kComputeUnits;
@@ -138,6 +180,7 @@ int choose(int Nb, int No, int64_t M)
     for (int i = 0; i < mdnn::variant_count(); ++i) {
         const mdnn::VariantInfo& v = mdnn::variant_info(i);
         if (!variant_usable(v, Nb, No)) continue;
+        if (!v.vec && Nb % 4 == 0 && No % 4 == 0) continue;      // 4-byte copies only where 16-byte ones cannot be used
         const double c = variant_cost(v, No, M);
         if (best < 0 || c < best_cost) { best = i; best_cost = c; }
     }
@@ -158,11 +201,23 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
     Geometry g;
     const mdnn_status gs = check_geometry(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &g);
     if (gs != MDNN_OK) return gs;
-    int v;
+    int  v;
+    char force_cut = 0;
     if (!variant || !variant[0] || std::strcmp(variant, "auto") == 0) {
         v = choose(Nb, No, g.M);
     } else {
-        v = find_variant(variant);
+        // "name" or "name:c" with c one of w h t q H T Q (see choose_cut)
+        char name[32];
+        const char* colon = std::strchr(variant, ':');
+        const size_t len = colon ? (size_t)(colon - variant) : std::strlen(variant);
+        if (len >= sizeof(name)) return MDNN_EINVAL;
+        std::memcpy(name, variant, len);
+        name[len] = 0;
+        if (colon) {
+            if (!colon[1] || colon[2] || !std::strchr("whtqHTQ", colon[1])) return MDNN_EINVAL;
+            force_cut = colon[1];
+        }
+        v = find_variant(name);
         if (v >= 0 && !variant_usable(mdnn::variant_info(v), Nb, No)) v = -1;
     }
     if (v < 0) return MDNN_EINVAL;
@@ -183,17 +238,32 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
     const int64_t n_tiles = (int64_t)p.n_otiles * p.n_mtiles;
     if (n_tiles > ((int64_t)1 << 26)) return MDNN_ETOOBIG;
     p.n_tiles = (int)n_tiles;
-    choose_split(vi, p.n_tiles, &p.n_whole, &p.split);
-    p.n_pieces = (p.n_tiles - p.n_whole) * p.split;
+    const Cut cut = choose_cut(vi, p.n_tiles, force_cut);
+    if (cut.n_whole < 0) return MDNN_EINVAL;                  // this kernel cannot cut a tile that way
+    p.n_whole = cut.n_whole;
+    p.n_half = cut.n_half;  p.n_third = cut.n_third;  p.n_quarter = cut.n_quarter;
+    p.n_pieces = cut.pieces();
     // Pieces go last, where the dispatcher deals them to whichever units free up first -- except
     // up to one per unit, which go FIRST.  A piece launched last runs alone on its unit, and a lone
     // small workgroup leaves the matrix pipe idle during every other instruction; launched first it
     // shares the unit with whole tiles, and the launch ends with whole tiles finishing together
     // (measured: +0.8 % on the 3x3 256-channel layer, +1 ... +3.4 % on layers with two to six rounds
-    // of tiles; -0.6 % with a single round of whole tiles, hence the condition).
-    p.n_first = p.n_whole >= 2 * kComputeUnits ? std::min(p.n_pieces, kComputeUnits) : 0;
-    p.first_per_xcd = div_up(p.n_first, 8);
-    p.last_per_xcd = div_up(p.n_pieces - p.n_first, 8);
+    // of tiles; -0.6 % with a single round of whole tiles, hence the condition).  The largest
+    // pieces are the ones that go first.
+    {
+        const int total[3] = {2 * p.n_half, 3 * p.n_third, 4 * p.n_quarter};
+        int room = p.n_whole >= 2 * kComputeUnits ? kComputeUnits : 0;
+        for (int c = 0; c < 3; ++c) {
+            const int f = std::min(total[c], room);
+            room -= f;
+            p.front.begin[c] = 0;         p.front.count[c] = f;            p.front.per_xcd[c] = div_up(f, 8);
+            p.back.begin[c] = f;          p.back.count[c] = total[c] - f;  p.back.per_xcd[c] = div_up(total[c] - f, 8);
+        }
+        for (mdnn::ConvParams::PieceRegion* r : {&p.front, &p.back}) {
+            r->wgs = 8 * (r->per_xcd[0] + r->per_xcd[1] + r->per_xcd[2]);
+            r->pieces = r->count[0] + r->count[1] + r->count[2];
+        }
+    }
     p.tiles_per_xcd = div_up(p.n_whole, 8);
     // 2-D visiting order of the column tiles (see ConvParams): needs tiles aligned with pixel rows
     p.row_tiles = 0;
@@ -242,7 +312,10 @@ uint64_t mdnn_conv_flops(int Nb, int Wo, int Ho, int Nc, int No, int Sk)
 
 const char* mdnn_status_string(mdnn_status s)
 {
-    switch (s) {
+    // a C caller may pass any int: read the bits without going through the enumeration's value range
+    int code;
+    std::memcpy(&code, &s, sizeof code);
+    switch (code) {
         case MDNN_OK:      return "ok";
         case MDNN_EINVAL:  return "invalid argument (dimension, stride, pad, alpha or variant name)";
         case MDNN_ENULL:   return "null pointer";
@@ -296,10 +369,15 @@ mdnn_status mdnn_describe_launch(int Nb, int Wi, int Hi, int Nc, int No, int Sk,
     if (ps != MDNN_OK) { text[0] = 0; return ps; }
     const mdnn::VariantInfo& vi = mdnn::variant_info(v);
     std::snprintf(text, text_size,
-                  "variant=%s tile=%dx%d kslab=%d threads=%d K=%d M=%d tiles=%d whole=%d split=%d pieces=%d "
+                  "variant=%s tile=%dx%d kslab=%d threads=%d K=%d M=%d tiles=%d whole=%d split=%d "
+                  "halved=%d thirded=%d quartered=%d pieces=%d "
                   "pieces_first=%d grid=%d lds_bytes=%u table_entries=%d",
                   vi.name, vi.tile_o, vi.tile_m, vi.kslab, vi.threads, p.K, p.M, p.n_tiles, p.n_whole,
-                  p.split, p.n_pieces, p.n_first, 8 * (p.first_per_xcd + p.tiles_per_xcd + p.last_per_xcd),
+                  // split: pieces per cut tile when all are cut alike (1 = none is cut), 0 = a mixture
+                  p.n_pieces == 0 ? 1 : (p.n_third == 0 && p.n_quarter == 0) ? 2 : (p.n_half == 0 && p.n_quarter == 0) ? 3
+                                    : (p.n_half == 0 && p.n_third == 0) ? 4 : 0,
+                  p.n_half, p.n_third, p.n_quarter, p.n_pieces, p.front.pieces,
+                  p.front.wgs + 8 * p.tiles_per_xcd + p.back.wgs,
                   mdnn::variant_lds_bytes(v, p.tab_cap), p.tab_cap);
     return MDNN_OK;
 }
@@ -342,8 +420,10 @@ mdnn_status bprop_plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int strid
     Geometry g;
     const mdnn_status gs = check_geometry(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &g);
     if (gs != MDNN_OK) return gs;
-    if (pad > Sk - 1) return MDNN_EINVAL;      // would need a negative pad in the transposed problem
-    if (stride == 1) {
+    // Stride 1 with pad <= Sk - 1 is one forward convolution with pad Sk - 1 - pad.  A larger pad
+    // would make that pad negative: such layers take the general path below (one residue class, the
+    // full correlation, then the gather picks din out of it), like every stride > 1.
+    if (stride == 1 && pad <= Sk - 1) {
         b->T = Sk;  b->filters_t = Nc;  b->pad_t = Sk - 1 - pad;
         b->He = Hi;  b->We = Wi;
         b->bank_bytes = (size_t)g.filt_bytes;
@@ -351,7 +431,8 @@ mdnn_status bprop_plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int strid
         b->total_bytes = b->e_offset;
         return MDNN_OK;
     }
-    const int T = (Sk + stride - 1) / stride;
+    const int T = (int)(((int64_t)Sk + stride - 1) / stride);
+    if ((int64_t)stride * stride >= ((int64_t)1 << 24)) return MDNN_ETOOBIG;      // (keeps the next product in range)
     const int64_t filters_t = (int64_t)stride * stride * Nc;
     if (filters_t >= ((int64_t)1 << 24)) return MDNN_ETOOBIG;
     b->T = T;  b->filters_t = (int)filters_t;  b->pad_t = T - 1;
@@ -457,7 +538,7 @@ mdnn_status bprop_data_enqueue(const BpropPlan& b, const float* dout, const floa
     if (ps != MDNN_OK) return ps;
     if (p.Ho != b.He || p.Wo != b.We) return MDNN_EINVAL;          // cannot happen: Ho + 2 pad_t - T + 1 == He
 
-    if (stride == 1) {
+    if (b.total_bytes == b.e_offset) {                             // no per-class results: the direct path
         if (mdnn::launch_flip_transpose(filt, bank, Nc, No, Sk * Sk, stream) != 0) return MDNN_ELAUNCH;
         p.in = dout;  p.filt = bank;  p.out = din;
         p.alpha = alpha;

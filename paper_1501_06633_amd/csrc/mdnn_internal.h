@@ -27,15 +27,25 @@ struct ConvParams {
     int n_otiles;        // tiles along No
     int n_mtiles;        // tiles along M
     int n_tiles;         // n_otiles * n_mtiles
-    // Tail balancing: tiles [0, n_whole) run whole; each of the last n_tiles - n_whole tiles is
-    // cut along the filter dimension into split (1, 2 or 4) pieces that run as separate workgroups.
+    // Tail balancing: tiles [0, n_whole) run whole; the last n_tiles - n_whole tiles are cut into
+    // pieces that run as separate workgroups: first n_half tiles in halves, then n_third tiles in
+    // thirds (48 + 48 + 32 filter rows of a 128-row tile), then n_quarter tiles in quarters.
+    // Pieces are numbered within their class (halves, pieces of thirded tiles, quarters).
     int n_whole;
-    int split;
-    int n_pieces;        // (n_tiles - n_whole) * split
+    int n_half, n_third, n_quarter;
+    int n_pieces;        // 2 n_half + 3 n_third + 4 n_quarter
     int tiles_per_xcd;   // ceil(n_whole / 8)
-    int n_first;         // pieces [0, n_first) are launched before the whole tiles, the others after them
-    int first_per_xcd;   // ceil(n_first / 8)
-    int last_per_xcd;    // ceil((n_pieces - n_first) / 8)
+    // Launch order: the `front` pieces, the whole tiles, the `back` pieces.  Within a region the
+    // classes follow each other, largest pieces first, and every class is dealt to the 8 XCDs in
+    // contiguous runs of per_xcd pieces (so every XCD gets its share of every size).
+    struct PieceRegion {
+        int begin[3];    // first piece of class c (0 halves, 1 thirds, 2 quarters) in this region
+        int count[3];    // pieces of class c in this region
+        int per_xcd[3];  // ceil(count / 8)
+        int wgs;         // 8 * (per_xcd[0] + per_xcd[1] + per_xcd[2]): workgroups the region occupies in the grid
+        int pieces;      // count[0] + count[1] + count[2]
+    };
+    PieceRegion front, back;
     // Column-tile order.  When a tile covers whole output pixels and a row of pixels is a whole
     // number of tiles (row_tiles > 0), column tiles are visited in strips of strip_rows image rows,
     // column by column inside a strip, so that the tiles in flight on one XCD form a compact 2-D
@@ -61,9 +71,26 @@ struct VariantInfo {
     float eff;           // sustained fraction of the matrix rate with many tiles per compute unit (measured)
     float eff_few;       // same with fewer than four tiles per compute unit: start-up and drain of
                          // co-resident workgroups coincide instead of overlapping (measured)
-    int max_split;       // 1, 2 or 4: finest cut of a tile this variant's kernel can run
+    int max_split;       // 1, 2 or 4: finest even cut of a tile this variant's kernel can run
+    int thirds;          // 1: the kernel can also run a tile as 48 + 48 + 32 filter rows
     int max_tab;         // most offset-table entries kept in LDS at once (longer K: several fills per tile)
 };
+
+// One instantiated kernel.  The translation units conv_variants_*.hip each hold a few of them
+// (so that they compile side by side); conv_fprop.hip strings their lists together.
+typedef void (*ConvKernelFn)(const ConvParams);
+struct VariantEntry {
+    VariantInfo  info;
+    ConvKernelFn fn;
+    uint32_t     ring_bytes;     // LDS of the operand ring; the offset table follows it
+};
+const VariantEntry* conv_variants_a(int* count);
+const VariantEntry* conv_variants_b(int* count);
+const VariantEntry* conv_variants_c(int* count);
+const VariantEntry* conv_variants_d(int* count);
+const VariantEntry* conv_variants_e(int* count);
+const VariantEntry* conv_variants_f(int* count);
+const VariantEntry* conv_variants_g(int* count);
 
 int                variant_count();
 const VariantInfo& variant_info(int i);

@@ -139,3 +139,34 @@ def make_matrices(N, M, K, seed, integer=False):
         b = rng.uniform(-1.0, 1.0, size=(K, M)).astype(np.float32)
         a = rng.standard_normal(size=(K, N), dtype=np.float32) * np.float32(0.01)
     return np.ascontiguousarray(a), np.ascontiguousarray(b)
+
+
+def stratified_points(rows, cols, tile_rows, tile_cols, per_tile, seed):
+    """Sample positions (row, col) of a rows x cols matrix so that every tile_rows x tile_cols tile of
+    its tiling (ragged last tiles included) holds at least ``per_tile`` (>= 2) of them: the tile's
+    first and last element, then uniform draws inside the tile.  Tiles are those of the coarsest
+    launch grid; a test that wants every piece of a cut tile covered passes the piece's size.
+    Returns an int64 array (npts, 2).  Index bookkeeping only: none of the method's arithmetic."""
+    rng = np.random.Generator(np.random.PCG64(SEED_BASE + 7000 + seed))
+    r0 = np.arange(0, rows, tile_rows, dtype=np.int64)
+    c0 = np.arange(0, cols, tile_cols, dtype=np.int64)
+    R0, C0 = np.meshgrid(r0, c0, indexing="ij")
+    R0, C0 = R0.ravel(), C0.ravel()
+    R1 = np.minimum(R0 + tile_rows, rows)          # exclusive ends
+    C1 = np.minimum(C0 + tile_cols, cols)
+    pts = [np.stack([R0, C0], axis=1), np.stack([R1 - 1, C1 - 1], axis=1)]
+    for _ in range(max(0, per_tile - 2)):
+        r = R0 + (rng.random(R0.size) * (R1 - R0)).astype(np.int64)
+        c = C0 + (rng.random(C0.size) * (C1 - C0)).astype(np.int64)
+        pts.append(np.stack([r, c], axis=1))
+    return np.concatenate(pts, axis=0)
+
+
+def output_points(layer_or_dims, Ho, Wo, tile_rows, tile_cols, per_tile, seed):
+    """``stratified_points`` over the output seen as the No x (Ho*Wo*Nb) matrix the kernels tile,
+    returned as (o, y, x, n) rows (int32) for the oracle's point-wise entry."""
+    No, Nb = layer_or_dims
+    rc = stratified_points(No, Ho * Wo * Nb, tile_rows, tile_cols, per_tile, seed)
+    o, m = rc[:, 0], rc[:, 1]
+    pix, n = m // Nb, m % Nb
+    return np.stack([o, pix // Wo, pix % Wo, n], axis=1).astype(np.int32)

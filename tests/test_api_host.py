@@ -95,6 +95,10 @@ def test_too_big(L):
     assert call(Nc=65536, Sk=3, No=4096) == B.MDNN_ETOOBIG                  # filt
     assert call(Nc=16384, Sk=4, No=2048, Hi=8, Wi=8, Nb=4) == B.MDNN_ETOOBIG   # filt = 2 GiB exactly
     assert call(Nb=2**20, Wi=2**20, Hi=2**20, Nc=2**20) == B.MDNN_ETOOBIG   # no wrap-around
+    # a very wide, shallow filter matrix: 2^26 filters of one tap are only 256 MiB, but the rows past
+    # the last one, which must read as zero, would have byte offsets that wrap back into the buffer
+    assert call(Nb=1, Wi=2, Hi=2, Nc=1, Sk=1, pad=0, No=2**26) == B.MDNN_ETOOBIG
+    assert B.mdnn_describe_launch(1, 2, 2, 1, 2**23, 1, 1, 0)["tiles"] > 0           # 2^23 filters fit
 
 
 def test_misaligned(L):
@@ -142,6 +146,23 @@ def test_choice_between_the_two_128x128_tiles_follows_the_tile_count(L):
         assert pick(Hi) == "o128m128k8", Hi
 
 
+def test_variant_choice_is_the_committed_one(L):
+    """The heuristic's choice (variant and tail cut) for 72 named shapes -- the five benchmark layers,
+    the paper's Table 1, a VGG-16 style network and a 48-shape grid -- equals the committed
+    snapshot, so that an edit to the cost model is visible as a diff of named shapes.  After a
+    deliberate change: python tests/golden/write_variant_choice.py."""
+    import importlib.util
+    path = os.path.join(ROOT, "tests", "golden", "write_variant_choice.py")
+    spec = importlib.util.spec_from_file_location("write_variant_choice", path)
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    want = open(os.path.join(ROOT, "tests", "golden", "variant_choice.txt")).read().splitlines()
+    got = mod.text().splitlines()
+    assert len(got) == len(want) == 1 + 5 + 10 + 9 + 48
+    for g, w in zip(got, want):
+        assert g == w
+
+
 def test_long_k_keeps_the_resident_workgroups(L):
     """The offset table is capped per variant so that LDS use, and with it the number of
     workgroups per CU, does not depend on K."""
@@ -161,7 +182,8 @@ def test_describe_launch(L):
     assert d["variant"] in B.mdnn_variant_names()
     to, tm = map(int, d["tile"].split("x"))
     assert d["tiles"] == -(-256 // to) * -(-d["M"] // tm)
-    assert d["whole"] + d["pieces"] // max(d["split"], 1) == d["tiles"]
+    assert d["whole"] + d["halved"] + d["thirded"] + d["quartered"] == d["tiles"]
+    assert d["pieces"] == 2 * d["halved"] + 3 * d["thirded"] + 4 * d["quartered"]
     assert d["lds_bytes"] <= 160 * 1024 and d["table_entries"] % d["kslab"] == 0
     # a pinned variant, a plan with the tail cut in pieces, and the error paths
     d = B.mdnn_describe_launch(128, 91, 6, 8, 128, 3, 1, 0, "o128m128")
@@ -170,6 +192,28 @@ def test_describe_launch(L):
         B.mdnn_describe_launch(8, 2, 2, 1, 1, 3, 1, 0)
     with pytest.raises(B.MdnnError):
         B.mdnn_describe_launch(8, 9, 9, 1, 4, 3, 1, 0, "nope")
+
+
+def test_how_the_last_round_is_cut(L):
+    """128 images, 128 filters, 3x3 unpadded: Ho * Wo tiles of 128x128.  What becomes of the
+    r = tiles mod 256 left-over tiles: quarters up to 64, thirds (48 + 48 + 32 rows; the deep-slab
+    kernel only) up to 85, halves up to 128, quarters (up to three per unit) up to 192, then
+    whole tiles."""
+    def cut(r, variant):
+        d = B.mdnn_describe_launch(128, 2 + 16, 2 + (16 + r // 16), 4, 128, 3, 1, 0, variant) if r % 16 == 0 else \
+            B.mdnn_describe_launch(128, 2 + 1, 2 + (256 + r), 4, 128, 3, 1, 0, variant)
+        assert d["tiles"] == 256 + r and d["whole"] + d["halved"] + d["thirded"] + d["quartered"] == d["tiles"]
+        return d["split"], d["halved"], d["thirded"], d["quartered"]
+    for v in ("o128m128", "o128m128k8"):
+        assert cut(0, v) == (1, 0, 0, 0)
+        assert cut(40, v) == (4, 0, 0, 40) and cut(64, v) == (4, 0, 0, 64)
+        assert cut(100, v) == (2, 100, 0, 0) and cut(128, v) == (2, 128, 0, 0)
+        assert cut(129, v) == (4, 0, 0, 129) and cut(176, v) == (4, 0, 0, 176) and cut(192, v) == (4, 0, 0, 192)
+        assert cut(200, v) == (1, 0, 0, 0) and cut(255, v) == (1, 0, 0, 0)
+    assert cut(65, "o128m128") == (3, 0, 65, 0) and cut(82, "o128m128") == (3, 0, 82, 0)
+    assert cut(85, "o128m128") == (3, 0, 85, 0) and cut(86, "o128m128") == (2, 86, 0, 0)
+    assert cut(82, "o128m128k8") == (2, 82, 0, 0)
+    assert cut(136, "o128m128") == (4, 0, 0, 136) and cut(136, "o128m128k8") == (4, 0, 0, 136)
     assert L.mdnn_describe_launch(8, 9, 9, 1, 4, 3, 1, 0, None, None, 0) == B.MDNN_ENULL
 
 
@@ -182,7 +226,10 @@ def test_bprop_data_workspace_and_argument_checks(L):
     st, n = B.mdnn_conv_bprop_data_workspace(128, 227, 227, 3, 96, 11, 4, 0)
     bank = 96 * 9 * 48 * 4
     assert st == B.MDNN_OK and n == ((bank + 255) // 256) * 256 + 48 * 57 * 57 * 128 * 4
-    assert B.mdnn_conv_bprop_data_workspace(8, 8, 8, 2, 4, 3, 1, 3)[0] == B.MDNN_EINVAL     # pad > Sk - 1
+    # stride 1 with pad > Sk - 1 goes the way of the strided layers: the turned-over bank, then the
+    # full correlation [Nc][Ho + Sk - 1][Wo + Sk - 1][Nb] out of which din is picked (Ho = Wo = 12)
+    st, n = B.mdnn_conv_bprop_data_workspace(8, 8, 8, 2, 4, 3, 1, 3)
+    assert st == B.MDNN_OK and n == 512 + 2 * 14 * 14 * 8 * 4          # the 288-byte bank rounded up to 256s
     assert B.mdnn_conv_bprop_data_workspace(8, 2, 2, 2, 4, 3, 1, 0)[0] == B.MDNN_EINVAL     # no output
     assert L.mdnn_conv_bprop_data_workspace(8, 8, 8, 2, 4, 3, 1, 1, None) == B.MDNN_ENULL
     args = (8, 8, 8, 2, 4, 3, 1, 1)
@@ -202,7 +249,6 @@ def test_static_data_gradient_argument_checks(L):
     assert call_s(d=None) == B.MDNN_ENULL and call_s(f=None) == B.MDNN_ENULL and call_s(o=None) == B.MDNN_ENULL
     assert call_s(a=float("nan")) == B.MDNN_EINVAL
     assert call_s(o=FAKE + 4) == B.MDNN_EALIGN
-    assert call_s(dims=(8, 8, 8, 2, 4, 3, 1, 3)) == B.MDNN_EINVAL          # stride 1 with pad > Sk - 1
     assert call_s(dims=(8, 2, 2, 2, 4, 3, 1, 0)) == B.MDNN_EINVAL          # no output
     # the limit is the header's constant, in terms of mdnn_conv_bprop_data_workspace()
     header = open(HEADER).read()

@@ -90,22 +90,20 @@ def test_strided_first_layer_gradient(env):
 
 @pytest.mark.parametrize("name", sorted(W.TABLE1))
 def test_paper_table1_shapes_sampled(env, name):
-    """The ten layer shapes of the paper's Table 1 at full size (minibatch 128): 20 000 sampled
-    elements of din plus its corners against the oracle's one-by-one evaluation.  The two
-    first layers (stride 4) go through the residue-class path."""
+    """The ten layer shapes of the paper's Table 1 at full size (minibatch 128): elements of din
+    sampled in every tile against the oracle's one-by-one evaluation.  The two first layers
+    (stride 4) go through the residue-class path."""
     _, B, oracle = env
     L, _ = W.TABLE1[name]
     say(f"[bprop-table1] layer={name} dims={L.dims()}")
     dout, filt = make_grad(L, oracle)
     got = run_gpu(env, L, dout, filt)
-    rng = np.random.default_rng(L.seed + 2)
-    npts = 20000
-    idx = np.stack([rng.integers(0, L.Nc, npts), rng.integers(0, L.Hi, npts),
-                    rng.integers(0, L.Wi, npts), rng.integers(0, L.Nb, npts)], axis=1).astype(np.int32)
-    idx[0] = (0, 0, 0, 0)
-    idx[1] = (L.Nc - 1, L.Hi - 1, L.Wi - 1, L.Nb - 1)
-    idx[2] = (L.Nc - 1, 0, L.Wi - 1, 0)
-    idx[3] = (0, L.Hi - 1, 0, L.Nb - 1)
+    # din seen as the Nc x (Hi*Wi*Nb) matrix the kernels tile: two points in every 16-row by
+    # 64-column block, block corners included -- no tile or tail piece of any tile shape (the
+    # narrowest is 32 rows by 128 columns; the strided layers pass through a gather that works
+    # on 4-column groups) is left without a sample
+    idx = W.output_points((L.Nc, L.Nb), L.Hi, L.Wi, 16, 64, 2, L.seed % 1000)
+    say(f"    {idx.shape[0]} points")
     vals, absum = oracle.conv_bprop_data_points(dout, filt, idx, (L.Hi, L.Wi), L.stride, L.pad, L.alpha)
     c, iy, ix, n = idx.T
     check(got[c, iy, ix, n], vals, absum, L.alpha, name)
@@ -128,6 +126,9 @@ ODD = [
     ("s2_odd_batch",    5,  9,  9,  3, 10, 3, 2, 1, 1.0),    # 4-byte gather
     ("s5_3x3_pad2",     8, 14, 14,  4,  8, 3, 5, 2, 1.0),    # most classes have no tap at all
     ("s2_one_window",   4,  6,  6,  3,  8, 6, 2, 0, 1.0),
+    ("pad_eq_sk",       8,  7,  9,  4, 12, 3, 1, 3, 1.0),    # stride 1, pad > Sk - 1: the general path with one class
+    ("pad_gt_sk_1x1",   4,  5,  5,  3,  8, 1, 1, 2, 0.5),    # 1x1 filter with an apron of two
+    ("s2_pad_gt_sk",    8,  8,  8,  4,  8, 2, 2, 3, 1.0),    # strided with pad > Sk - 1
 ]
 
 

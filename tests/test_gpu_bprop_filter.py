@@ -93,8 +93,8 @@ def test_layer_gradient_integer_bitwise(env, name):
 
 @pytest.mark.parametrize("name", sorted(W.TABLE1))
 def test_paper_table1_shapes_sampled(env, name):
-    """The ten layer shapes of the paper's Table 1 at full size (minibatch 128): 20 000 sampled
-    elements of dfilt plus its corners against the oracle's one-by-one evaluation.  K reaches
+    """The ten layer shapes of the paper's Table 1 at full size (minibatch 128): elements of dfilt
+    sampled in every tile against the oracle's one-by-one evaluation.  K reaches
     9216 and No 1024 here (72 x 8 tiles), so the contraction is not cut at all for the largest."""
     _, B, oracle = env
     L, _ = W.TABLE1[name]
@@ -102,14 +102,13 @@ def test_paper_table1_shapes_sampled(env, name):
     say(f"[bprop-filter-table1] layer={name} dims={L.dims()} ranges={need // (L.Nc * L.Sk * L.Sk * L.No * 4)}")
     inp, dout = make_pair(L, oracle)
     got = run_gpu(env, L, inp, dout)
-    rng = np.random.default_rng(L.seed + 1)
-    npts = 20000
-    idx = np.stack([rng.integers(0, L.Nc, npts), rng.integers(0, L.Sk, npts),
-                    rng.integers(0, L.Sk, npts), rng.integers(0, L.No, npts)], axis=1).astype(np.int32)
-    idx[0] = (0, 0, 0, 0)
-    idx[1] = (L.Nc - 1, L.Sk - 1, L.Sk - 1, L.No - 1)
-    idx[2] = (L.Nc - 1, 0, L.Sk - 1, 0)
-    idx[3] = (0, L.Sk - 1, 0, L.No - 1)
+    # dfilt seen as the K x No matrix the kernel tiles (128 rows by 128 / 96 / 64 / 32 columns): two
+    # points in every 16 x 16 block, block corners included, so no tile goes without a sample
+    K = L.Nc * L.Sk * L.Sk
+    rc = W.stratified_points(K, L.No, 16, 16, 2, L.seed % 1000)
+    k, o = rc[:, 0], rc[:, 1]
+    idx = np.stack([k // (L.Sk * L.Sk), (k // L.Sk) % L.Sk, k % L.Sk, o], axis=1).astype(np.int32)
+    say(f"    {idx.shape[0]} points")
     vals, absum = oracle.conv_bprop_filter_points(inp, dout, idx, L.Sk, L.stride, L.pad, L.alpha)
     c, ky, kx, o = idx.T
     check(got[c, ky, kx, o], vals, absum, L.alpha, name)

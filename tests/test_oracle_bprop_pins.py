@@ -20,6 +20,9 @@ CASES = [
     (4, 2, 6, 6, 3, 3, 1, 2),      # pad = Sk - 1
     (1, 2, 11, 11, 2, 11, 4, 0),   # one window
     (2, 3, 12, 9, 4, 3, 4, 1),     # stride larger than the filter: gaps in the gradient
+    (2, 2, 5, 6, 3, 3, 1, 3),      # pad = Sk: the outermost windows lie wholly in the apron
+    (3, 2, 4, 4, 2, 1, 1, 2),      # 1x1 filter with an apron of two
+    (2, 2, 7, 7, 3, 2, 2, 3),      # strided, pad > Sk - 1
 ]
 
 
