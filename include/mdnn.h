@@ -121,14 +121,17 @@ const char* mdnn_choose_variant(int Nb, int Wi, int Hi, int Nc, int No,
  * call accepts is accepted (a stride-1 layer with pad > Sk - 1 takes the same
  * route as a strided one).  `workspace` is device memory of at least the size
  * mdnn_conv_bprop_data_workspace() reports (16-byte aligned); it receives the
- * rearranged filter bank and, for stride > 1, the per-residue-class results
- * that a last kernel interleaves into din (input pixels are split by
- * (iy + pad, ix + pad) modulo the stride; every class is a stride-1 problem with
- * a ceil(Sk/stride)^2 sub-filter, and all classes run as one convolution).  It
- * may be reused or freed once the stream has passed this call.  Same stream,
- * ownership and error rules as mdnn_conv_fprop, with one difference: the call
- * enqueues two or three kernels, and MDNN_ELAUNCH can be returned after the
- * first of them was enqueued (din and the workspace are then undefined).
+ * rearranged filter bank, nothing else: for stride > 1 the input pixels are
+ * split by (iy + pad, ix + pad) modulo the stride, every class is a stride-1
+ * problem with a ceil(Sk/stride)^2 sub-filter, all classes run as one
+ * convolution, and that convolution stores each value straight to its
+ * interleaved place in din.  The workspace may be reused or freed once the
+ * stream has passed this call.  Same stream, ownership and error rules as
+ * mdnn_conv_fprop, with one difference: the call enqueues two or three kernels,
+ * and MDNN_ELAUNCH can be returned after the first of them was enqueued (din and
+ * the workspace are then undefined).  MDNN_ETOOBIG also where the classes' common
+ * grid, (Ho + T - 1)(Wo + T - 1) Nb s^2 Nc values with T = ceil(Sk/stride), reaches
+ * 2^32 bytes (it is the kernel's index space, not memory).
  */
 mdnn_status mdnn_conv_bprop_data_workspace(int Nb, int Wi, int Hi, int Nc, int No,
                                            int Sk, int stride, int pad, size_t* bytes);
@@ -147,8 +150,7 @@ mdnn_status mdnn_conv_bprop_data(const float* dout, const float* filt, float* di
  * nothing and uses no memset.  A problem whose workspace
  * (mdnn_conv_bprop_data_workspace()) exceeds MDNN_STATIC_SCRATCH_BYTES is
  * refused with MDNN_ETOOBIG before anything is enqueued: the limit covers the
- * rearranged bank of every stride-1 layer up to 1024 x 1024 filters of 3 x 3,
- * and strided layers whose per-class results fit beside their bank.
+ * rearranged bank of every layer up to 1024 x 1024 filters of 3 x 3.
  * All calls on one GPU share that GPU's array, which keeps whatever the last
  * call left in it (every call overwrites all it reads, nothing has to start
  * at zero): calls that overlap in time on one GPU -- different streams, or two

@@ -16,7 +16,10 @@
 // inserted zeros per value; instead the input pixels are split by the residue
 // class of (iy + pad, ix + pad) modulo s, every class is a stride-1 correlation
 // of dout with its own ceil(Sk/s)^2 sub-filter, all classes run as one forward
-// convolution with s*s*Nc filters, and a gather interleaves the classes into din.
+// convolution with s*s*Nc filters, and that convolution's epilogue stores every
+// value straight to its interleaved place in din (the kernel's scatter mode), so
+// the per-class results never exist in memory; the few pixels beyond the last
+// window, which no class reaches, are set to zero by a small kernel here.
 #include <hip/hip_runtime.h>
 
 #include <mutex>
@@ -26,8 +29,7 @@
 namespace mdnn {
 namespace {
 
-// Workspace of the allocation-free data-gradient entry point: the rearranged filter bank (and,
-// for stride > 1, the per-class results) of one call.  One copy per GPU, held from the moment
+// Workspace of the allocation-free data-gradient entry point: the rearranged filter bank of one call.  One copy per GPU, held from the moment
 // the library's code is loaded there until the process ends.  In host code this name is only a
 // handle for hipGetSymbolAddress(); the device address it yields is what kernels are given.
 constexpr size_t kStaticScratchBytes = MDNN_STATIC_SCRATCH_BYTES;
@@ -91,32 +93,29 @@ __global__ void __launch_bounds__(256) class_filters(const float* __restrict__ f
     }
 }
 
-// din[c][iy][ix][n] = E[cls*Nc + c][(iy+pad)/s][(ix+pad)/s][n], cls = ((iy+pad)%s)*s + (ix+pad)%s;
-// 0 for pixels beyond the last window (their quotient lies outside E).  E is [s*s*Nc][He][We][Nb].
-template <int VW>
-__global__ void __launch_bounds__(256) gather_classes(const float* __restrict__ e, float* __restrict__ din,
-                                                      int Nc, int Hi, int Wi, int Nb, int He, int We,
-                                                      int stride, int pad)
+// din[c][iy][ix][n] = 0 for the pixels beyond the last window (iy >= y_end or ix >= x_end): no
+// residue class has a value for them, so the scattering convolution never writes them.
+__global__ void __launch_bounds__(256) zero_unreached(float* __restrict__ din, int Nc, int Hi, int Wi, int Nb,
+                                                      int y_end, int x_end)
 {
-    typedef float vec __attribute__((ext_vector_type(VW)));
-    const int    nbv   = Nb / VW;
-    const size_t total = (size_t)Nc * Hi * Wi * nbv;
+    // the bottom strip of every channel (whole rows), then the right strip of the rows above it
+    const size_t bottom = (size_t)(Hi - y_end) * Wi * Nb;             // per channel
+    const size_t right  = (size_t)y_end * (Wi - x_end) * Nb;          // per channel
+    const size_t total  = (size_t)Nc * (bottom + right);
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
          i += (size_t)gridDim.x * blockDim.x) {
-        const int    n   = (int)(i % nbv);
-        const size_t pix = i / nbv;
-        const int    ix  = (int)(pix % Wi);
-        const size_t r   = pix / Wi;
-        const int    iy  = (int)(r % Hi);
-        const int    c   = (int)(r / Hi);
-        const int    qy  = (iy + pad) / stride, ry = (iy + pad) - qy * stride;
-        const int    qx  = (ix + pad) / stride, rx = (ix + pad) - qx * stride;
-        vec v = 0.0f;
-        if (qy < He && qx < We) {
-            const size_t row = (size_t)(ry * stride + rx) * Nc + c;
-            v = reinterpret_cast<const vec*>(e)[((row * He + qy) * We + qx) * nbv + n];
+        const size_t c = i / (bottom + right);
+        size_t       r = i - c * (bottom + right);
+        size_t       e;
+        if (r < bottom) {
+            e = ((size_t)c * Hi + y_end) * Wi * Nb + r;
+        } else {
+            r -= bottom;
+            const size_t per_row = (size_t)(Wi - x_end) * Nb;
+            const size_t iy = r / per_row;
+            e = (((size_t)c * Hi + iy) * Wi + x_end) * Nb + (r - iy * per_row);
         }
-        reinterpret_cast<vec*>(din)[i] = v;
+        din[e] = 0.0f;
     }
 }
 
@@ -159,19 +158,16 @@ int launch_class_filters(const float* filt, float* fc, int Nc, int No, int Sk, i
     return (int)hipGetLastError();
 }
 
-int launch_gather_classes(const float* e, float* din, int Nc, int Hi, int Wi, int Nb, int He, int We,
-                          int stride, int pad, void* stream)
+int launch_zero_unreached(float* din, int Nc, int Hi, int Wi, int Nb, int y_end, int x_end, void* stream)
 {
-    const int    vw    = (Nb % 4 == 0) ? 4 : 1;
-    const size_t total = (size_t)Nc * Hi * Wi * (Nb / vw);
+    if (y_end > Hi) y_end = Hi;
+    if (x_end > Wi) x_end = Wi;
+    const size_t total = (size_t)Nc * ((size_t)(Hi - y_end) * Wi + (size_t)y_end * (Wi - x_end)) * Nb;
+    if (total == 0) return 0;
     size_t blocks = (total + 255) / 256;
-    if (blocks > 256u * 64u) blocks = 256u * 64u;
-    if (vw == 4)
-        hipLaunchKernelGGL(gather_classes<4>, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
-                           e, din, Nc, Hi, Wi, Nb, He, We, stride, pad);
-    else
-        hipLaunchKernelGGL(gather_classes<1>, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
-                           e, din, Nc, Hi, Wi, Nb, He, We, stride, pad);
+    if (blocks > 256u * 64u) blocks = 256u * 64u;          // grid-stride beyond that
+    hipLaunchKernelGGL(zero_unreached, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       din, Nc, Hi, Wi, Nb, y_end, x_end);
     return (int)hipGetLastError();
 }
 

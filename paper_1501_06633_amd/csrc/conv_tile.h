@@ -466,6 +466,74 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
     const int o_wave = o0 + wo * (RA * MB);
     const int m_wave = m0 + wm * (RB * MB);
     auto block_row = [](int a, int v) { return MB == 32 ? a * 32 + 8 * (v >> 2) + (v & 3) : a * 16 + v; };
+    if (p.scat_stride) {
+        // Scatter mode (see ConvParams): row o of the problem is a (residue class, channel) pair and
+        // column m a (pixel, image) of the class's own grid; the value goes straight to its place in
+        // the interleaved tensor, so the per-class results never exist in memory.  Where each row of
+        // the tile goes is worked out once per tile into LDS (the operand ring is free by now).
+        int* const row_c  = reinterpret_cast<int*>(lds);          // channel, or -1 for a row past the last
+        int* const row_dy = row_c + TO;                           // ry - pad
+        int* const row_dx = row_dy + TO;                          // rx - pad
+        static_assert(3 * TO * 4 <= (int)C::ring_bytes, "row table fits the ring");
+        __syncthreads();
+        for (int r = t; r < TO; r += NT) {
+            const int o = o0 + r;
+            int c = -1, dy = 0, dx = 0;
+            if (o < p.No) {
+                const int cls = o / p.scat_Nc;
+                const int ry  = cls / p.scat_stride;
+                c  = o - cls * p.scat_Nc;
+                dy = ry - p.scat_pad;
+                dx = (cls - ry * p.scat_stride) - p.scat_pad;
+            }
+            row_c[r] = c;  row_dy[r] = dy;  row_dx[r] = dx;
+        }
+        __syncthreads();
+        // this lane's columns: with 16-byte copies its RB columns are images of one pixel
+        constexpr int NCOL = (VW == 4) ? 1 : RB;
+        int  cy[NCOL], cx[NCOL], cn[NCOL];
+        bool cok[NCOL];
+#pragma unroll
+        for (int b = 0; b < NCOL; ++b) {
+            const int m = m_wave + lb * RB + b;
+            cok[b] = m < p.M;
+            const int pix = (int)fast_div((uint32_t)(cok[b] ? m : 0), p.nb_magic, p.nb_shift);
+            const int qy  = (int)fast_div((uint32_t)pix, p.wo_magic, p.wo_shift);
+            cn[b] = (cok[b] ? m : 0) - pix * p.Nb;
+            cy[b] = qy * p.scat_stride;
+            cx[b] = (pix - qy * p.Wo) * p.scat_stride;
+        }
+#pragma unroll
+        for (int a = 0; a < RA; ++a) {
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const int r  = wo * (RA * MB) + block_row(a, v) + 4 * kg;
+                const int c  = row_c[r];
+                const int dy = row_dy[r], dx = row_dx[r];
+#pragma unroll
+                for (int b = 0; b < NCOL; ++b) {
+                    const int iy = cy[b] + dy, ix = cx[b] + dx;
+                    const bool ok = cok[b] & (c >= 0) & ((uint32_t)iy < (uint32_t)p.scat_Hi) & ((uint32_t)ix < (uint32_t)p.scat_Wi);
+                    if (!ok) continue;
+                    // fewer than 2^30 elements: 32-bit index arithmetic cannot wrap
+                    const uint32_t e = (((uint32_t)c * (uint32_t)p.scat_Hi + (uint32_t)iy) * (uint32_t)p.scat_Wi + (uint32_t)ix) *
+                                           (uint32_t)p.Nb + (uint32_t)cn[b];
+                    if constexpr (VW == 4) {
+                        BVec w;
+#pragma unroll
+                        for (int bb = 0; bb < RB; ++bb) {
+                            if constexpr (RB == 1) w = p.alpha * acc[a][0][v];
+                            else w[bb] = p.alpha * acc[a][bb][v];
+                        }
+                        *reinterpret_cast<BVec*>(p.out + e) = w;
+                    } else {
+                        p.out[e] = p.alpha * acc[a][b][v];
+                    }
+                }
+            }
+        }
+        return;
+    }
     if (o0 + TO <= p.No && m0 + TM <= p.M) {
         const uint32_t lane_off = ((uint32_t)(4 * kg) * (uint32_t)p.M + (uint32_t)(lb * RB)) * 4u;
         const size_t   row_bytes = (size_t)p.M * 4u;

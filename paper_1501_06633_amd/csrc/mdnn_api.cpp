@@ -278,6 +278,7 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
     }
     const int kpad = div_up(g.K, vi.kslab) * vi.kslab;
     p.tab_cap = kpad < vi.max_tab ? kpad : vi.max_tab;
+    p.scat_stride = 0;  p.scat_Nc = 0;  p.scat_Hi = 0;  p.scat_Wi = 0;  p.scat_pad = 0;
     p.in_bytes = (uint32_t)g.in_bytes;
     p.filt_bytes = (uint32_t)g.filt_bytes;
     p.alpha = 0.0f;
@@ -402,17 +403,17 @@ mdnn_status mdnn_sgemm_tn(const float* a, const float* b, float* c,
 namespace {
 
 // Geometry of the forward convolution whose stride-1 run yields the data gradient.
-// stride 1: the turned-over bank (K' = No*Sk*Sk rows, Nc columns), pad Sk-1-pad, written to din.
-// stride s: T = ceil(Sk/s); the residue-class bank (No*T*T rows, s*s*Nc columns), pad T-1, written
-//           to E [s*s*Nc][Ho+T-1][Wo+T-1][Nb] in the workspace, then gathered into din.
+// stride 1, pad <= Sk - 1: the turned-over bank (K' = No*Sk*Sk rows, Nc columns), pad Sk-1-pad, written to din.
+// otherwise: T = ceil(Sk/s); the residue-class bank (No*T*T rows, s*s*Nc columns), pad T-1, over a grid
+//           of (Ho+T-1) x (Wo+T-1) pixels per class, scattered into din by the kernel's epilogue.
 struct BpropPlan {
-    int       T;               // taps per side of the transposed problem (Sk for stride 1)
+    bool      direct;          // the first of the two forms
+    int       T;               // taps per side of the transposed problem (Sk for the direct form)
     int       filters_t;       // its filter count (Nc, or s*s*Nc)
     int       pad_t;           // its pad
-    int       He, We;          // its output extent (Hi x Wi for stride 1)
+    int       He, We;          // its output extent (Hi x Wi for the direct form)
     size_t    bank_bytes;      // rearranged filter bank
-    size_t    e_offset;        // byte offset of E in the workspace (stride > 1)
-    size_t    total_bytes;
+    size_t    total_bytes;     // workspace: the bank, rounded up to 256 bytes
 };
 
 mdnn_status bprop_plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int pad, BpropPlan* b)
@@ -421,28 +422,29 @@ mdnn_status bprop_plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int strid
     const mdnn_status gs = check_geometry(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &g);
     if (gs != MDNN_OK) return gs;
     // Stride 1 with pad <= Sk - 1 is one forward convolution with pad Sk - 1 - pad.  A larger pad
-    // would make that pad negative: such layers take the general path below (one residue class, the
-    // full correlation, then the gather picks din out of it), like every stride > 1.
+    // would make that pad negative: such layers take the general form (one residue class, the
+    // full correlation, of which the epilogue keeps what lies inside din), like every stride > 1.
     if (stride == 1 && pad <= Sk - 1) {
+        b->direct = true;
         b->T = Sk;  b->filters_t = Nc;  b->pad_t = Sk - 1 - pad;
         b->He = Hi;  b->We = Wi;
         b->bank_bytes = (size_t)g.filt_bytes;
-        b->e_offset = (b->bank_bytes + 255) & ~(size_t)255;
-        b->total_bytes = b->e_offset;
+        b->total_bytes = (b->bank_bytes + 255) & ~(size_t)255;
         return MDNN_OK;
     }
     const int T = (int)(((int64_t)Sk + stride - 1) / stride);
     if ((int64_t)stride * stride >= ((int64_t)1 << 24)) return MDNN_ETOOBIG;      // (keeps the next product in range)
     const int64_t filters_t = (int64_t)stride * stride * Nc;
     if (filters_t >= ((int64_t)1 << 24)) return MDNN_ETOOBIG;
+    b->direct = false;
     b->T = T;  b->filters_t = (int)filters_t;  b->pad_t = T - 1;
     b->He = g.Ho + T - 1;  b->We = g.Wo + T - 1;
     const int64_t bank_bytes = 4 * (int64_t)No * T * T * filters_t;
-    const int64_t e_bytes = 4 * filters_t * b->He * b->We * Nb;
-    if (bank_bytes >= kFourGiB / 2 || e_bytes >= kFourGiB) return MDNN_ETOOBIG;
+    // the per-class grid is only ever a column index of the kernel: it has to stay below 2^31 columns
+    const int64_t columns = (int64_t)b->He * b->We * Nb;
+    if (bank_bytes >= kFourGiB / 2 || columns * 4 >= kFourGiB) return MDNN_ETOOBIG;
     b->bank_bytes = (size_t)bank_bytes;
-    b->e_offset = (b->bank_bytes + 255) & ~(size_t)255;
-    b->total_bytes = b->e_offset + (size_t)e_bytes;
+    b->total_bytes = (b->bank_bytes + 255) & ~(size_t)255;
     return MDNN_OK;
 }
 
@@ -529,7 +531,6 @@ mdnn_status bprop_data_enqueue(const BpropPlan& b, const float* dout, const floa
     Geometry g;
     check_geometry(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &g);       // succeeded inside bprop_plan
     float* bank = static_cast<float*>(workspace);
-    float* e    = reinterpret_cast<float*>(static_cast<char*>(workspace) + b.e_offset);
 
     // the transposed problem: No input channels of Ho x Wo, b.filters_t filters of T x T, stride 1
     mdnn::ConvParams p;
@@ -538,18 +539,20 @@ mdnn_status bprop_data_enqueue(const BpropPlan& b, const float* dout, const floa
     if (ps != MDNN_OK) return ps;
     if (p.Ho != b.He || p.Wo != b.We) return MDNN_EINVAL;          // cannot happen: Ho + 2 pad_t - T + 1 == He
 
-    if (b.total_bytes == b.e_offset) {                             // no per-class results: the direct path
+    p.in = dout;  p.filt = bank;  p.out = din;
+    p.alpha = alpha;
+    if (b.direct) {
         if (mdnn::launch_flip_transpose(filt, bank, Nc, No, Sk * Sk, stream) != 0) return MDNN_ELAUNCH;
-        p.in = dout;  p.filt = bank;  p.out = din;
-        p.alpha = alpha;
         return mdnn::launch_variant(v, p, stream) == 0 ? MDNN_OK : MDNN_ELAUNCH;
     }
     if (mdnn::launch_class_filters(filt, bank, Nc, No, Sk, stride, b.T, stream) != 0) return MDNN_ELAUNCH;
-    p.in = dout;  p.filt = bank;  p.out = e;
-    p.alpha = alpha;
-    if (mdnn::launch_variant(v, p, stream) != 0) return MDNN_ELAUNCH;
-    return mdnn::launch_gather_classes(e, din, Nc, Hi, Wi, Nb, b.He, b.We, stride, pad, stream) == 0
-               ? MDNN_OK : MDNN_ELAUNCH;
+    // pixels with (iy + pad) / stride >= He (or the same along x) belong to no class's grid
+    const int64_t y_end = (int64_t)stride * b.He - pad, x_end = (int64_t)stride * b.We - pad;
+    if (mdnn::launch_zero_unreached(din, Nc, Hi, Wi, Nb, (int)std::max<int64_t>(0, std::min<int64_t>(y_end, Hi)),
+                                    (int)std::max<int64_t>(0, std::min<int64_t>(x_end, Wi)), stream) != 0)
+        return MDNN_ELAUNCH;
+    p.scat_stride = stride;  p.scat_Nc = Nc;  p.scat_Hi = Hi;  p.scat_Wi = Wi;  p.scat_pad = pad;
+    return mdnn::launch_variant(v, p, stream) == 0 ? MDNN_OK : MDNN_ELAUNCH;
 }
 
 }  // namespace

@@ -54,6 +54,12 @@ struct ConvParams {
     int row_tiles;       // tiles per row of output pixels
     int strip_rows;
     int tab_cap;         // offset-table entries resident in LDS at once (multiple of the K slab)
+    // Scatter mode of the epilogue (scat_stride > 0), used by the data gradient of strided layers:
+    // the problem's "filters" are (residue class, channel) pairs, row o = cls * scat_Nc + c with
+    // cls = ry * scat_stride + rx, and the value at output pixel (qy, qx) belongs to
+    // out[c][qy * scat_stride + ry - scat_pad][qx * scat_stride + rx - scat_pad][n] of a
+    // [scat_Nc][scat_Hi][scat_Wi][Nb] tensor (dropped where that pixel does not exist).
+    int scat_stride, scat_Nc, scat_Hi, scat_Wi, scat_pad;
     uint32_t in_bytes;   // byte size of in   (buffer-resource range: loads beyond it return 0)
     uint32_t filt_bytes; // byte size of filt
     float alpha;
@@ -107,8 +113,8 @@ int launch_mfma_probe(float* sink, int blocks, int waves_per_block, int iters, v
 // Layout kernels of the data gradient (bprop_data.hip); return hipSuccess (0) or the HIP error code.
 int launch_flip_transpose(const float* filt, float* ft, int Nc, int No, int SkSk, void* stream);
 int launch_class_filters(const float* filt, float* fc, int Nc, int No, int Sk, int stride, int T, void* stream);
-int launch_gather_classes(const float* e, float* din, int Nc, int Hi, int Wi, int Nb, int He, int We,
-                          int stride, int pad, void* stream);
+// din[c][iy][ix][n] = 0 for iy >= y_end or ix >= x_end (the pixels no window reaches)
+int launch_zero_unreached(float* din, int Nc, int Hi, int Wi, int Nb, int y_end, int x_end, void* stream);
 
 // Device address, on the current GPU, of the static array of MDNN_STATIC_SCRATCH_BYTES bytes behind
 // mdnn_conv_bprop_data_static (bprop_data.hip); looked up once per GPU.  Returns 0 or a HIP error code.

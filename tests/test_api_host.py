@@ -221,15 +221,14 @@ def test_bprop_data_workspace_and_argument_checks(L):
     # stride 1: only the rearranged filter bank (Nc*Sk*Sk*No floats), rounded up to 256 bytes
     st, n = B.mdnn_conv_bprop_data_workspace(64, 56, 56, 256, 256, 3, 1, 1)
     assert st == B.MDNN_OK and n == 256 * 9 * 256 * 4
-    # stride 4, 11x11: 16 residue classes with 3x3 sub-filters -> a bank of (96*9) x (16*3) floats, and
-    # the per-class results [16*3][55+2][55+2][128] that are then gathered into din
+    # stride 4, 11x11: 16 residue classes with 3x3 sub-filters -> a bank of (96*9) x (16*3) floats;
+    # the per-class results go straight into din and need no room
     st, n = B.mdnn_conv_bprop_data_workspace(128, 227, 227, 3, 96, 11, 4, 0)
     bank = 96 * 9 * 48 * 4
-    assert st == B.MDNN_OK and n == ((bank + 255) // 256) * 256 + 48 * 57 * 57 * 128 * 4
-    # stride 1 with pad > Sk - 1 goes the way of the strided layers: the turned-over bank, then the
-    # full correlation [Nc][Ho + Sk - 1][Wo + Sk - 1][Nb] out of which din is picked (Ho = Wo = 12)
+    assert st == B.MDNN_OK and n == ((bank + 255) // 256) * 256
+    # stride 1 with pad > Sk - 1 goes the way of the strided layers: one class, the turned-over bank
     st, n = B.mdnn_conv_bprop_data_workspace(8, 8, 8, 2, 4, 3, 1, 3)
-    assert st == B.MDNN_OK and n == 512 + 2 * 14 * 14 * 8 * 4          # the 288-byte bank rounded up to 256s
+    assert st == B.MDNN_OK and n == 512                                 # the 288-byte bank rounded up to 256s
     assert B.mdnn_conv_bprop_data_workspace(8, 2, 2, 2, 4, 3, 1, 0)[0] == B.MDNN_EINVAL     # no output
     assert L.mdnn_conv_bprop_data_workspace(8, 8, 8, 2, 4, 3, 1, 1, None) == B.MDNN_ENULL
     args = (8, 8, 8, 2, 4, 3, 1, 1)
@@ -257,8 +256,9 @@ def test_static_data_gradient_argument_checks(L):
     fits = (128, 12, 12, 1024, 1024, 3, 1, 1)        # bank of 36 MiB
     assert B.mdnn_conv_bprop_data_workspace(*fits)[1] <= B.MDNN_STATIC_SCRATCH_BYTES
     assert call_s(dims=fits, o=FAKE + 4) == B.MDNN_EALIGN                   # passed the size check
-    for too_big in [(128, 227, 227, 3, 96, 11, 4, 0),                       # per-class results of 80 MB
-                    (128, 12, 12, 1024, 1280, 3, 1, 1)]:                    # bank of 45 MiB
+    assert call_s(dims=(128, 227, 227, 3, 96, 11, 4, 0), o=FAKE + 4) == B.MDNN_EALIGN    # a strided layer fits too
+    for too_big in [(128, 12, 12, 1024, 1280, 3, 1, 1),                     # bank of 45 MiB
+                    (16, 40, 40, 256, 512, 11, 4, 0)]:                      # 16 classes x 3x3 x 256 x 512: 72 MiB
         assert B.mdnn_conv_bprop_data_workspace(*too_big)[1] > B.MDNN_STATIC_SCRATCH_BYTES
         assert call_s(dims=too_big) == B.MDNN_ETOOBIG
 

@@ -2,8 +2,8 @@
 workspace entry point it is a variant of (mdnn_conv_bprop_data), through the C ABI: same kernels,
 same plan, so the two results must be equal bit for bit; and against the oracle to the usual
 bound.  Two calls in a row on the same GPU, the second with a smaller problem (the static array
-still holds the first call's bank), then a strided layer whose per-class results live in the
-array too, then the size limit."""
+still holds the first call's bank), then a strided layer (whose per-class results go straight
+to the result tensor), then the size limit."""
 import sys
 
 import numpy as np
@@ -76,8 +76,8 @@ def test_two_calls_in_a_row_second_smaller(env):
 
 
 def test_strided_layer_results_in_static_array(env):
-    """Stride 2: the residue-class results pass through the static array as well; then a smaller
-    stride-1 call right after it."""
+    """Stride 2: the residue-class filter bank lives in the static array and the results are
+    scattered into din; then a smaller stride-1 call right after it."""
     strided = W.custom("static_strided", 16, 21, 19, 8, 24, 5, 2, 1, 1.0, seed=W.SEED_BASE + 4243)
     after = W.custom("static_after", 4, 7, 7, 4, 8, 3, 1, 0, 2.0, seed=W.SEED_BASE + 4244)
     for L, seed in ((strided, 13), (after, 14)):
@@ -90,7 +90,7 @@ def test_strided_layer_results_in_static_array(env):
 def test_limit_is_an_error_not_a_launch(env):
     """A problem whose workspace exceeds the static array is refused before anything is enqueued."""
     torch, B, _ = env
-    L = W.LAYERS["conv1"]                                       # per-class results: 80 MB
+    L = W.custom("bank_45_mib", 128, 12, 12, 1024, 1280, 3, 1, 1)
     st, need = B.mdnn_conv_bprop_data_workspace(L.Nb, L.Wi, L.Hi, L.Nc, L.No, L.Sk, L.stride, L.pad)
     assert st == 0 and need > B.MDNN_STATIC_SCRATCH_BYTES
     tiny = torch.zeros(64, device="cuda")
