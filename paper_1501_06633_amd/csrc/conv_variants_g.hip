@@ -1,4 +1,4 @@
-// Tile shapes of the FPROP convolution kernel, group g: tiles of 16 x 16 matrix blocks: 48 filter rows.
+// Tile shapes of the FPROP convolution kernel, group g: the 48-row tile of 16 x 16 matrix blocks, and the wide tile for output-bound layers.
 // Columns of a shape: waves along filters x along columns, matrix blocks per wave along filters x
 // along columns, slab depth, ring stages, floats per copy, barrier k-step, block edge.
 // An entry: name, workgroups that fit one compute unit, measured fraction of the matrix rate with
@@ -11,11 +11,16 @@ namespace {
 
 //          WO WM RA RB KS NS VW JB MB
 typedef Cfg<1, 4, 3, 4, 16, 3, 4, 2, 16> C_o48m256;
+// eight waves of 32 x 128 (32 x 32 blocks): 2 KB of every output row per tile, for contractions so
+// short that the layer is bound by writing its output
+typedef Cfg<2, 4, 1, 4, 8, 3, 4, 2, 32> C_o64m512;
 
 const VariantEntry kGroup[] = {
     // 57 KB ring + 8 KB table: two workgroups per CU
     // (48 filters of 3x3x96 over 57x57x128 outputs: 79 % against 62 % for the best of the 32-row-block tiles)
     make_entry<C_o48m256>("o48m256", 2, 0.79f, 0.75f, 1024),
+    // chosen by rule (K <= 64), not by cost: rated so that the cost model never picks it elsewhere
+    make_entry<C_o64m512>("o64m512", 2, 0.50f, 0.50f, 64),
 };
 
 }  // namespace

@@ -13,6 +13,8 @@ namespace {
 constexpr int     kComputeUnits = 256;          // MI355X
 constexpr int     kStripRows = 8;               // image rows per strip of the 2-D tile order
 constexpr int64_t kFourGiB = (int64_t)1 << 32;
+constexpr int     kWideTileMaxK = 64;           // ... and below this the 64 x 512 tile is taken
+constexpr int     kStreamOutMaxK = 128;         // contractions this short are bound by writing the output
 constexpr int     kMaxSlab = 64;                // no tile variant stages more rows of k than this at once
 
 struct Geometry {
@@ -173,8 +175,18 @@ double variant_cost(const mdnn::VariantInfo& v, int No, int64_t M)
     return rounds * v.tile_o * v.tile_m / eff;
 }
 
-int choose(int Nb, int No, int64_t M)
+int find_variant(const char* name);
+
+int choose(int Nb, int No, int64_t M, int64_t K)
 {
+    // Output-bound layers (a contraction of a few dozen terms: 54 FLOPs per 4 bytes written at
+    // K = 27) want long contiguous pieces of every output row per tile and many waves in flight,
+    // not matrix-core efficiency: the 64 x 512 tile (3 -> 64 channels at 224 x 224: 41 -> 45.6 %
+    // of the matrix peak, which is 5.1 TB/s written).
+    if (K <= kWideTileMaxK && No > 32 && Nb % 4 == 0 && No % 4 == 0 && M >= 512 * 2 * kComputeUnits) {
+        const int wide = find_variant("o64m512");
+        if (wide >= 0) return wide;
+    }
     int    best = -1;
     double best_cost = 0;
     for (int i = 0; i < mdnn::variant_count(); ++i) {
@@ -204,7 +216,7 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
     int  v;
     char force_cut = 0;
     if (!variant || !variant[0] || std::strcmp(variant, "auto") == 0) {
-        v = choose(Nb, No, g.M);
+        v = choose(Nb, No, g.M, g.K);
     } else {
         // "name" or "name:c" with c one of w h t q H T Q (see choose_cut)
         char name[32];
@@ -279,6 +291,7 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
     const int kpad = div_up(g.K, vi.kslab) * vi.kslab;
     p.tab_cap = kpad < vi.max_tab ? kpad : vi.max_tab;
     p.scat_stride = 0;  p.scat_Nc = 0;  p.scat_Hi = 0;  p.scat_Wi = 0;  p.scat_pad = 0;
+    p.stream_out = g.K <= kStreamOutMaxK ? 1 : 0;
     p.in_bytes = (uint32_t)g.in_bytes;
     p.filt_bytes = (uint32_t)g.filt_bytes;
     p.alpha = 0.0f;
@@ -339,7 +352,7 @@ const char* mdnn_choose_variant(int Nb, int Wi, int Hi, int Nc, int No, int Sk, 
 {
     Geometry g;
     if (check_geometry(Nb, Wi, Hi, Nc, No, Sk, stride, pad, &g) != MDNN_OK) return nullptr;
-    const int v = choose(Nb, No, g.M);
+    const int v = choose(Nb, No, g.M, g.K);
     return v < 0 ? nullptr : mdnn::variant_info(v).name;
 }
 
