@@ -216,6 +216,10 @@ def main():
     ap.add_argument("--table1", action="store_true",
                     help="also time the ten layer shapes of the paper's Table 1 (minibatch 128, synthetic "
                          "data) and print MI355X efficiency beside the paper's GTX 980 column")
+    ap.add_argument("--variant-sweep", action="store_true",
+                    help="time every 16-byte tile variant on 48 layer shapes (minibatch 16 ... 128, 7x7 ... 56x56 "
+                         "pixels, 96 ... 512 channels, 3x3) and report how far the library's own choice is from "
+                         "the best of them")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy three times (known HBM traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -518,6 +522,45 @@ def main():
                     log(f"[bench] table1 {name:18s} bprop-{kind}: {g['ms']:8.4f} ms {g['tflops']:7.2f} TFLOP/s "
                         f"{100 * g['frac_peak']:5.1f}% of peak")
         result["table1"] = rows
+
+    if args.variant_sweep:
+        def timed(fn, n):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+        rows, worst = {}, 0.0
+        for nb in (16, 32, 64, 128):
+            for hw in (7, 14, 28, 56):
+                for nc, no in ((96, 256), (256, 384), (512, 512)):
+                    d_in = torch.rand((nc, hw, hw, nb), device="cuda") - 0.5
+                    d_f = torch.randn((nc, 3, 3, no), device="cuda") * 0.01
+                    out = torch.empty((no, hw, hw, nb), device="cuda")
+                    fl = B.mdnn_conv_flops(nb, hw, hw, nc, no, 3)
+                    auto = B.mdnn_choose_variant(nb, hw, hw, nc, no, 3, 1, 1)
+                    res = {}
+                    for v in B.mdnn_variant_names():
+                        if v.endswith("s") or v == "o64m512":            # 4-byte copies; the output-bound tile
+                            continue
+                        fn = lambda: B.mdnn_conv_fprop(d_in, d_f, 1, 1, 1.0, out=out, variant=v)
+                        w = timed(fn, 3)
+                        timed(fn, int(30.0 / max(w, 1e-3)) + 1)
+                        res[v] = min(timed(fn, 10), timed(fn, 10))
+                    best = min(res, key=res.get)
+                    loss = res[auto] / res[best] - 1.0
+                    worst = max(worst, loss)
+                    name = f"nb{nb}.{hw}x{hw}.{nc}to{no}"
+                    rows[name] = {"auto": auto, "auto_frac_peak": round(fl / res[auto] / 1e9 / PEAK_FP32_MATRIX_TFLOPS, 4),
+                                  "best": best, "best_frac_peak": round(fl / res[best] / 1e9 / PEAK_FP32_MATRIX_TFLOPS, 4),
+                                  "auto_slower_by": round(loss, 4)}
+                    log(f"[bench] sweep {name:24s} auto {auto:11s} {100 * rows[name]['auto_frac_peak']:5.1f}%   "
+                        f"best {best:11s} {100 * rows[name]['best_frac_peak']:5.1f}%   auto slower by {100 * loss:4.1f}%")
+                    del d_in, d_f, out
+        result["variant_sweep"] = {"shapes": rows, "worst_auto_slower_by": round(worst, 4)}
+        log(f"[bench] sweep: the library's choice is at most {100 * worst:.1f}% slower than the best variant")
 
     if args.vgg16:
         # the nine distinct 3x3 shapes of a VGG-16 style network at minibatch 64; random data made on

@@ -11,7 +11,8 @@
 namespace {
 
 constexpr int     kComputeUnits = 256;          // MI355X
-constexpr int     kStripRows = 8;               // image rows per strip of the 2-D tile order
+constexpr int     kStripRows = 8;               // image rows per strip of the 2-D tile order (measured: 4 and 8 fetch
+                                                // least through L2, 2 and 16 about 15-35 % more, row-major 50 % more)
 constexpr int64_t kFourGiB = (int64_t)1 << 32;
 constexpr int     kWideTileMaxK = 64;           // ... and below this the 64 x 512 tile is taken
 constexpr int     kStreamOutMaxK = 128;         // contractions this short are bound by writing the output
@@ -134,7 +135,12 @@ Cut choose_cut(const mdnn::VariantInfo& v, int n_tiles, char force = 0)
         if (cost < c.cost - 0.05) { c.cost = cost;  c.n_half = nh;  c.n_third = nt;  c.n_quarter = nq; }
     };
     take(rounds_of(2) / e2, r, 0, 0);
-    if (v.thirds && 3 * r <= kComputeUnits) take(0.375 / e3, 0, r, 0);
+    // Thirds only beside at most one round of whole tiles.  With two rounds on a kernel that holds
+    // two workgroups per unit, piece and first whole tile end together, both slots of every unit
+    // free at once, and the dispatcher then places the second round two to a unit on half the
+    // units (588 tiles of 128 x 128: 64.6 % of peak against 84.5 % with halves on the
+    // three-per-unit kernel).
+    if (v.thirds && 3 * r <= kComputeUnits && n_tiles < 2 * kComputeUnits) take(0.375 / e3, 0, r, 0);
     if (v.max_split >= 4) take(rounds_of(4) / e4, 0, 0, r);
     if (c.pieces() > 0) c.n_whole = n_tiles - r;
     return c;

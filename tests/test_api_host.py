@@ -213,6 +213,9 @@ def test_how_the_last_round_is_cut(L):
     assert cut(65, "o128m128") == (3, 0, 65, 0) and cut(82, "o128m128") == (3, 0, 82, 0)
     assert cut(85, "o128m128") == (3, 0, 85, 0) and cut(86, "o128m128") == (2, 86, 0, 0)
     assert cut(82, "o128m128k8") == (2, 82, 0, 0)
+    # thirds only beside at most one round of whole tiles: 512 + 76 tiles are halved
+    d = B.mdnn_describe_launch(128, 2 + 1, 2 + 588, 4, 128, 3, 1, 0, "o128m128")
+    assert (d["tiles"], d["whole"], d["split"], d["halved"]) == (588, 512, 2, 76)
     assert cut(136, "o128m128") == (4, 0, 0, 136) and cut(136, "o128m128k8") == (4, 0, 0, 136)
     assert L.mdnn_describe_launch(8, 9, 9, 1, 4, 3, 1, 0, None, None, 0) == B.MDNN_ENULL
 
