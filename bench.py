@@ -37,13 +37,13 @@ WARM_MS_FLOOR = 100.0
 TRAFFIC_SOURCE = "profiles/conv_fprop_hbm_traffic_pmc.txt"
 PLAN_KEYS = ("variant", "tiles", "whole", "halved", "thirded", "quartered", "pieces_first", "table_entries")
 RECORDED_TRAFFIC = {
-    "vgg":   {"bytes": 756.6e6, "plan": {"variant": "o128m128k8", "tiles": 3136, "whole": 3072, "halved": 0, "thirded": 0,
+    "vgg":   {"bytes": 762.5e6, "plan": {"variant": "o128m128k8", "tiles": 3136, "whole": 3072, "halved": 0, "thirded": 0,
                                          "quartered": 64, "pieces_first": 256, "table_entries": 2304}},
-    "conv1": {"bytes": 307.4e6, "plan": {"variant": "o96m256", "tiles": 1513, "whole": 1513, "halved": 0, "thirded": 0,
+    "conv1": {"bytes": 312.0e6, "plan": {"variant": "o96m256", "tiles": 1513, "whole": 1513, "halved": 0, "thirded": 0,
                                          "quartered": 0, "pieces_first": 0, "table_entries": 368}},
-    "conv2": {"bytes": 313.1e6, "plan": {"variant": "o128m128k8", "tiles": 1458, "whole": 1280, "halved": 0, "thirded": 0,
+    "conv2": {"bytes": 320.8e6, "plan": {"variant": "o128m128k8", "tiles": 1458, "whole": 1280, "halved": 0, "thirded": 0,
                                          "quartered": 178, "pieces_first": 256, "table_entries": 2400}},
-    "conv3": {"bytes": 107.9e6, "plan": {"variant": "o128m128", "tiles": 507, "whole": 507, "halved": 0, "thirded": 0,
+    "conv3": {"bytes": 108.4e6, "plan": {"variant": "o128m128", "tiles": 507, "whole": 507, "halved": 0, "thirded": 0,
                                          "quartered": 0, "pieces_first": 0, "table_entries": 2304}},
 }
 
@@ -573,9 +573,19 @@ def main():
             out = torch.empty((Lv.No, Lv.Hi, Lv.Wi, Lv.Nb), device="cuda")
             ms, _ = time_layer(torch, B, Lv, d_in, d_f, out, 20, 3, None, min_warm_ms=WARM_MS_FLOOR)
             fl = B.mdnn_conv_flops(Lv.Nb, Lv.Wi, Lv.Hi, Lv.Nc, Lv.No, Lv.Sk)
+            nbytes = 4 * (Lv.Nc * Lv.Hi * Lv.Wi * Lv.Nb + Lv.Nc * Lv.Sk * Lv.Sk * Lv.No + Lv.No * Lv.Hi * Lv.Wi * Lv.Nb)
             rows[name] = {"ms": round(ms, 4), "tflops": round(fl / ms / 1e9, 2),
                           "frac_peak": round(fl / ms / 1e9 / PEAK_FP32_MATRIX_TFLOPS, 4),
                           "variant": B.mdnn_choose_variant(Lv.Nb, Lv.Wi, Lv.Hi, Lv.Nc, Lv.No, Lv.Sk, Lv.stride, Lv.pad)}
+            # which roof binds: FLOPs per compulsory byte against the ridge 157.3 TFLOP/s / 8 TB/s = 19.7
+            if fl / nbytes < PEAK_FP32_MATRIX_TFLOPS * 1e3 / PEAK_HBM_GBS:
+                gbs = nbytes / ms / 1e6
+                rows[name]["roofline"] = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                          "frac": round(gbs / PEAK_HBM_GBS, 4), "algorithmic_bytes": nbytes,
+                                          "written_GBps": round(4 * Lv.No * Lv.Hi * Lv.Wi * Lv.Nb / ms / 1e6, 1)}
+            else:
+                rows[name]["roofline"] = {"bound": "mfma", "achieved": rows[name]["tflops"], "peak": PEAK_FP32_MATRIX_TFLOPS,
+                                          "unit": "TFLOP/s", "frac": rows[name]["frac_peak"]}
             tot_ms += ms
             tot_fl += fl
             log(f"[bench] vgg16 {name:8s} {Lv.Nc:4d}->{Lv.No:4d} @{Lv.Hi:3d}: {ms:8.4f} ms {fl / ms / 1e9:7.2f} TFLOP/s "

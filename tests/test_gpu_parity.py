@@ -162,6 +162,27 @@ def test_vgg16_shapes_sampled(env, name):
     check(got, vals, absum, L.alpha, name)
 
 
+def test_output_bound_first_layer_integer_bitwise(env):
+    """The 3 -> 64 channel first layer of the VGG-16 style network at full size (K = 27: bound by
+    writing its 822 MB output; 64 x 512 tiles, stores with the non-temporal hint): integer data,
+    points in every tile, bit for bit."""
+    torch, B, oracle = env
+    L = W.VGG16["conv1_1"]
+    plan = B.mdnn_describe_launch(L.Nb, L.Wi, L.Hi, L.Nc, L.No, L.Sk, L.stride, L.pad)
+    say(f"[parity-first-layer] plan={plan}")
+    assert plan["variant"] == "o64m512" and plan["tile"] == "64x512"
+    inp, filt = W.make_int_inputs(L)
+    out = B.mdnn_conv_fprop(torch.from_numpy(inp).cuda(), torch.from_numpy(filt).cuda(), L.stride, L.pad, L.alpha)
+    torch.cuda.synchronize()
+    idx = tile_points(B, L, tuple(out.shape), 27)
+    t = torch.from_numpy(idx.astype(np.int64)).cuda()
+    got = out[t[:, 0], t[:, 1], t[:, 2], t[:, 3]].cpu().numpy()
+    del out
+    vals, _ = oracle.conv_fprop_points(inp, filt, idx, L.stride, L.pad, L.alpha)
+    np.testing.assert_array_equal(got, vals)
+    assert np.abs(vals).max() > 0
+
+
 # ------------------------------------------------------- odd shapes, all variants
 ODD = [
     # name              Nb  Hi  Wi  Nc  No  Sk st pad alpha
