@@ -370,13 +370,16 @@ def main():
         # the headline layer's geometry at other minibatch sizes (Section 3.4 of the paper: its kernel
         # exists for minibatches of 64 and 128 only); flat-column tiles take any multiple of 4
         rows = {}
-        for nb in (4, 8, 16, 32, 64, 128, 256):
-            name = f"{args.workload}_nb{nb}"
-            W.LAYERS[name] = W.custom(name, nb, L.Hi, L.Wi, L.Nc, L.No, L.Sk, L.stride, L.pad, L.alpha)
+        # 50 and 100 are not multiples of 4: those take the 4-byte-copy tiles (Table 1's caption: sizes off
+        # the block size cost efficiency), and so does a filter count of No - 6 at the layer's own minibatch
+        for nb, no in [(n, L.No) for n in (4, 8, 16, 32, 50, 64, 100, 128, 256)] + [(L.Nb, L.No - 6)]:
+            name = f"{args.workload}_nb{nb}_no{no}"
+            W.LAYERS[name] = W.custom(name, nb, L.Hi, L.Wi, L.Nc, no, L.Sk, L.stride, L.pad, L.alpha)
             r, _ = layer_report(torch, B, W, name, 30, 5, None, min_warm_ms=WARM_MS_FLOOR)
             del W.LAYERS[name]
-            rows[str(nb)] = {"ms": r["ms"], "tflops": r["tflops"], "frac_peak": r["frac_peak"], "variant": r["variant"]}
-            log(f"[bench] minibatch {nb:4d}: {r['ms']:8.4f} ms {r['tflops']:7.2f} TFLOP/s "
+            key = str(nb) if no == L.No else f"{nb}, No={no}"
+            rows[key] = {"ms": r["ms"], "tflops": r["tflops"], "frac_peak": r["frac_peak"], "variant": r["variant"]}
+            log(f"[bench] minibatch {key:>12s}: {r['ms']:8.4f} ms {r['tflops']:7.2f} TFLOP/s "
                 f"{100 * r['frac_peak']:5.1f}%  variant={r['variant']}")
         result["minibatch"] = rows
 

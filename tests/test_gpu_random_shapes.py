@@ -77,3 +77,39 @@ def test_long_contractions_every_variant_bitwise():
             np.testing.assert_array_equal(y.cpu().numpy(), want, err_msg=f"{what} variant={v}")
             runs += 1
     assert runs == 40 * len(B.mdnn_variant_names())
+
+
+def test_pinned_cuts_on_random_shapes_bitwise():
+    """Thirty seeded mid-size shapes whose tiles are all cut, or whose last round is cut, in every way
+    a kernel offers (halves, 48 + 48 + 32-row thirds, quarters; pinned through the variant name):
+    ragged filter counts, ragged column counts, pads and strides, integer data, bit for bit."""
+    import torch
+    from paper_1501_06633_amd import binding as B
+    import oracle
+
+    pinned = ["o128m128:H", "o128m128:T", "o128m128:Q", "o128m128:t", "o128m128k8:H", "o128m128k8:Q",
+              "o96m256:H", "o96m256:h", "o64m256k8:H", "o64m256k8:Q", "o64m256k8:q", "o48m256:w", "o64m512:w"]
+    rng = np.random.default_rng(4096)
+    runs = 0
+    for it in range(30):
+        Nb = int(rng.choice([4, 8, 16, 32, 64]))
+        Sk = int(rng.choice([1, 3, 3, 5]))
+        stride = int(rng.integers(1, 3))
+        pad = int(rng.integers(0, Sk))
+        Hi = int(rng.integers(max(Sk, 6), 20))
+        Wi = int(rng.integers(max(Sk, 6), 20))
+        Nc = int(rng.integers(1, 12))
+        No = int(rng.choice([40, 100, 128, 132, 200, 256, 300]))
+        alpha = float(rng.choice([1.0, 0.5]))
+        x = rng.integers(-4, 5, size=(Nc, Hi, Wi, Nb)).astype(np.float32)
+        w = rng.integers(-4, 5, size=(Nc, Sk, Sk, No)).astype(np.float32)
+        want = oracle.conv_fprop(x, w, stride, pad, alpha, want_abs=False)
+        d_x, d_w = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+        what = f"case={it} Nb={Nb} Hi={Hi} Wi={Wi} Nc={Nc} No={No} Sk={Sk} stride={stride} pad={pad} alpha={alpha}"
+        print(what, flush=True)
+        for v in pinned:
+            y = B.mdnn_conv_fprop(d_x, d_w, stride, pad, alpha, variant=v)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(y.cpu().numpy(), want, err_msg=f"{what} variant={v}")
+            runs += 1
+    assert runs == 30 * len(pinned)
