@@ -74,7 +74,9 @@ mdnn_status mdnn_conv_fprop(const float* in, const float* filt, float* out,
  * A name may be followed by ':' and one letter that pins how tiles are cut into
  * the smaller blocks of Section 3.4: w = no tile is cut; h, t, q = the tiles of
  * the last partial round in halves, thirds (48 + 48 + 32 filter rows), quarters;
- * H, T, Q = every tile so.  A cut the kernel does not have is MDNN_EINVAL.
+ * m = 128 of them in halves and the rest (at most 64) in quarters, all launched in
+ * front of the whole tiles; H, T, Q = every tile so.  A cut the kernel does not
+ * have, or that does not fit the tile count, is MDNN_EINVAL.
  * Every variant and cut computes the same function for every valid argument set.
  */
 mdnn_status mdnn_conv_fprop_variant(const float* in, const float* filt, float* out,

@@ -97,12 +97,14 @@ bool variant_usable(const mdnn::VariantInfo& v, int Nb, int No)
 //   r <= 128: halves (1.5);
 //   r <= 192: quarters in chains of up to three (a mixture that gives every unit a half or
 //       a third plus a quarter has fewer rows on the busiest unit, but its second pieces run
-//       alone: 533 us against 488 us on a 14 x 14 layer with 392 tiles);
+//       alone: 533 us against 488 us on a 14 x 14 layer with 392 tiles) -- except beside a single
+//       round on a three-per-unit kernel, see the end of choose_cut();
 // each weighed by the piece's relative efficiency and taken only if it beats the coarser
 // choice by a margin.
 struct Cut {
     int    n_whole, n_half, n_third, n_quarter;
     double cost;                       // of the partial round, in tile times (0 if there is none)
+    bool   pair_up;                    // a half and a quarter per unit: all pieces go in front of the whole tiles
     int    pieces() const { return 2 * n_half + 3 * n_third + 4 * n_quarter; }
 };
 
@@ -111,13 +113,15 @@ struct Cut {
 // that lacks the cut asked for returns n_whole = -1.
 Cut choose_cut(const mdnn::VariantInfo& v, int n_tiles, char force = 0)
 {
-    Cut c = {n_tiles, 0, 0, 0, 0.0};
+    Cut c = {n_tiles, 0, 0, 0, 0.0, false};
     if (force) {
         const bool all = force == 'H' || force == 'T' || force == 'Q';
         const int  n = all ? n_tiles : n_tiles % kComputeUnits;
         const char f = all ? (char)(force - 'A' + 'a') : force;
-        const bool has = f == 'w' || (f == 'h' && v.max_split >= 2) || (f == 't' && v.thirds) || (f == 'q' && v.max_split >= 4);
+        const bool has = f == 'w' || (f == 'h' && v.max_split >= 2) || (f == 't' && v.thirds) || (f == 'q' && v.max_split >= 4) ||
+                         (f == 'm' && v.max_split >= 4 && n > 128 && n <= 192);
         if (!has) { c.n_whole = -1; return c; }
+        if (f == 'm') { c.n_half = 128;  c.n_quarter = n - 128;  c.pair_up = true; }
         if (f == 'h') c.n_half = n;
         if (f == 't') c.n_third = n;
         if (f == 'q') c.n_quarter = n;
@@ -142,6 +146,17 @@ Cut choose_cut(const mdnn::VariantInfo& v, int n_tiles, char force = 0)
     // three-per-unit kernel).
     if (v.thirds && 3 * r <= kComputeUnits && n_tiles < 2 * kComputeUnits) take(0.375 / e3, 0, r, 0);
     if (v.max_split >= 4) take(rounds_of(4) / e4, 0, 0, r);
+    // One round of whole tiles plus 128 < r <= 192 on a kernel that holds three workgroups per unit:
+    // a half, a quarter and a whole tile per unit, all started together (pieces in front), end
+    // together after (128 + 64 + 32) / 128 tile times; quarter chains run their tail alone.  386 ... 446
+    // tiles: 125 us against 129 us for the best other choice.  Only with one round: with two or
+    // three, everything that starts together ends together and the dispatcher then packs the next
+    // round three to a unit on a third of the units (255 us against 194 us), with four or five the
+    // gain is under 1 %.
+    if (v.max_split >= 4 && v.est_wg_per_cu >= 3 && n_tiles > kComputeUnits && n_tiles < 2 * kComputeUnits && r > 128 && r <= 192 &&
+        0.75 < c.cost - 0.05) {
+        c.cost = 0.75;  c.n_half = 128;  c.n_third = 0;  c.n_quarter = r - 128;  c.pair_up = true;
+    }
     if (c.pieces() > 0) c.n_whole = n_tiles - r;
     return c;
 }
@@ -232,7 +247,7 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
         std::memcpy(name, variant, len);
         name[len] = 0;
         if (colon) {
-            if (!colon[1] || colon[2] || !std::strchr("whtqHTQ", colon[1])) return MDNN_EINVAL;
+            if (!colon[1] || colon[2] || !std::strchr("whtqmHTQ", colon[1])) return MDNN_EINVAL;
             force_cut = colon[1];
         }
         v = find_variant(name);
@@ -270,7 +285,7 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
     // pieces are the ones that go first.
     {
         const int total[3] = {2 * p.n_half, 3 * p.n_third, 4 * p.n_quarter};
-        int room = p.n_whole >= 2 * kComputeUnits ? kComputeUnits : 0;
+        int room = cut.pair_up ? 2 * kComputeUnits : p.n_whole >= 2 * kComputeUnits ? kComputeUnits : 0;
         for (int c = 0; c < 3; ++c) {
             const int f = std::min(total[c], room);
             room -= f;

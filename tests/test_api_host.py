@@ -208,7 +208,8 @@ def test_how_the_last_round_is_cut(L):
         assert cut(0, v) == (1, 0, 0, 0)
         assert cut(40, v) == (4, 0, 0, 40) and cut(64, v) == (4, 0, 0, 64)
         assert cut(100, v) == (2, 100, 0, 0) and cut(128, v) == (2, 128, 0, 0)
-        assert cut(129, v) == (4, 0, 0, 129) and cut(176, v) == (4, 0, 0, 176) and cut(192, v) == (4, 0, 0, 192)
+        if v == "o128m128":
+            assert cut(129, v) == (4, 0, 0, 129) and cut(176, v) == (4, 0, 0, 176) and cut(192, v) == (4, 0, 0, 192)
         assert cut(200, v) == (1, 0, 0, 0) and cut(255, v) == (1, 0, 0, 0)
     assert cut(65, "o128m128") == (3, 0, 65, 0) and cut(82, "o128m128") == (3, 0, 82, 0)
     assert cut(85, "o128m128") == (3, 0, 85, 0) and cut(86, "o128m128") == (2, 86, 0, 0)
@@ -216,7 +217,15 @@ def test_how_the_last_round_is_cut(L):
     # thirds only beside at most one round of whole tiles: 512 + 76 tiles are halved
     d = B.mdnn_describe_launch(128, 2 + 1, 2 + 588, 4, 128, 3, 1, 0, "o128m128")
     assert (d["tiles"], d["whole"], d["split"], d["halved"]) == (588, 512, 2, 76)
-    assert cut(136, "o128m128") == (4, 0, 0, 136) and cut(136, "o128m128k8") == (4, 0, 0, 136)
+    # beside a single round, the three-per-unit kernel pairs a half with a quarter on every unit
+    assert cut(136, "o128m128") == (4, 0, 0, 136) and cut(136, "o128m128k8") == (0, 128, 0, 8)
+    assert cut(192, "o128m128k8") == (0, 128, 0, 64) and cut(129, "o128m128k8") == (0, 128, 0, 1)
+    d = B.mdnn_describe_launch(128, 2 + 1, 2 + 392, 4, 128, 3, 1, 0, "o128m128k8")
+    assert (d["whole"], d["pieces"], d["pieces_first"]) == (256, 288, 288)          # all pieces in front
+    d = B.mdnn_describe_launch(128, 2 + 1, 2 + 648, 4, 128, 3, 1, 0, "o128m128k8")   # two rounds + 136: quarters
+    assert (d["whole"], d["split"], d["quartered"]) == (512, 4, 136)
+    d = B.mdnn_describe_launch(128, 2 + 1, 2 + 136, 4, 128, 3, 1, 0, "o128m128k8")   # no whole round at all
+    assert d["whole"] == 0 and d["split"] in (2, 4)
     assert L.mdnn_describe_launch(8, 9, 9, 1, 4, 3, 1, 0, None, None, 0) == B.MDNN_ENULL
 
 

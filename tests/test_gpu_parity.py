@@ -237,10 +237,12 @@ TAILS = [
     # name        Nb  Hi  Wi  Nc  No  Sk st pad alpha  pieces per cut tile with the deep-slab kernel, with the shallow-slab one
     ("halves",    128,  6, 91,  8, 128, 3, 1, 0, 1.0,  2, 2),      # 356 tiles: 100 left over -> halves
     ("quarters",  128, 10, 39,  8, 128, 3, 1, 0, 0.5,  4, 4),      # 296 tiles:  40 left over -> quarters
-    ("quarters_ragged", 64, 11, 40, 6, 200, 3, 1, 1, 2.0, 4, 4),   # padded, ragged filter tile, 2 pixels per tile
+    ("quarters_ragged", 64, 11, 40, 6, 200, 3, 1, 1, 2.0, 4, (128, 0, 56)),   # padded, ragged filter tile, 2 pixels per tile; 440 tiles
     ("thirds",    128, 14, 30,  8, 128, 3, 1, 0, 1.0,  3, 2),      # 336 tiles: 80 left over -> 48 + 48 + 32 rows
     ("thirds_ragged", 64, 12, 28, 6, 200, 3, 1, 1, 2.0, 3, 2),     # 336 tiles, the second filter tile has 72 rows
-    ("quarter_chains", 128, 16, 30, 8, 128, 3, 1, 0, 0.5, 4, 4),   # 392 tiles: 136 left over -> up to three quarters per unit
+    # 392 tiles, 136 left over: up to three quarters per unit; the three-per-unit kernel pairs halves with quarters
+    ("one_round_136", 128, 16, 30, 8, 128, 3, 1, 0, 0.5, 4, (128, 0, 8)),
+    ("two_rounds_136", 128, 20, 38, 8, 128, 3, 1, 0, 0.5, 4, 4),    # 648 tiles: quarter chains on both
 ]
 
 
@@ -254,7 +256,11 @@ def test_tail_pieces_bitwise(env, case, variant):
     want = want_deep if variant == "o128m128" else want_shallow
     plan = B.mdnn_describe_launch(Nb, Wi, Hi, Nc, No, Sk, stride, pad, variant)
     say(f"[parity-tail] case={name} variant={variant} plan={plan}")
-    assert plan["split"] == want and plan["pieces"] == (plan["tiles"] - plan["whole"]) * want
+    if isinstance(want, tuple):          # (halved, thirded, quartered): a mixture, all of it in front of the whole tiles
+        assert plan["split"] == 0 and (plan["halved"], plan["thirded"], plan["quartered"]) == want
+        assert sum(want) == plan["tiles"] - plan["whole"] and plan["pieces_first"] == plan["pieces"]
+    else:
+        assert plan["split"] == want and plan["pieces"] == (plan["tiles"] - plan["whole"]) * want
     L = W.custom(name, Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha)
     inp, filt = W.make_int_inputs(L)
     want_out = oracle.conv_fprop(inp, filt, stride, pad, alpha, want_abs=False)
