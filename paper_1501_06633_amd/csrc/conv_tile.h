@@ -100,7 +100,7 @@ struct Cfg {
     static_assert(VW == 1 || VW == 4, "VW");
     static_assert(MB == 32 || MB == 16, "MB");
     static_assert(NT % MG == 0 && KS % BROWS == 0 && KS % KB == 0, "tile shape");
-    static_assert(A_EL % 64 == 0, "whole waves only may be masked off in the filter copy");
+    static_assert(A_EL % 32 == 0, "the filter copy masks off whole waves and, in the last wave that copies, the upper lanes");
     static_assert(RB == 1 || RB == 2 || RB == 4, "RB");
     static_assert(RA >= 1 && RA <= 4, "RA");
     // NS >= 3: slab s+1 must already be in flight when slab s reaches its barrier
@@ -216,6 +216,7 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
             if ((C::A_EL % NT) != 0 && wave * 64 + i * NT >= C::A_EL) continue;   // wave-uniform
+            if (C::A_EL % 64 != 0 && wave * 64 + i * NT + lane >= C::A_EL) continue;   // last wave of the slab: lower lanes only
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 rfl, LDS_PTR(dma_base + (st * STAGE_BYTES + i * NT * ACCESS)), C::VW * 4,
                 (int)voffA[i], 0, 0, 0);
@@ -643,6 +644,18 @@ template <class C> struct ThirdOf {
                   "the last 32 rows run as the fourth quarter piece");
 };
 
+// A 128-row tile cut into eight pieces of 16 rows: one 16-row matrix block per wave, all waves
+// side by side along the columns.  For launches that leave a CU a sixteenth to an eighth of a tile
+// beyond the pieces it already has (392 tiles on 256 units: a whole tile, a half and, on a quarter
+// of the units, one of these).
+template <class C> struct EighthOf {
+    static_assert(C::TO == 128 && C::MB == 32 && C::KS % 4 == 0, "eighths exist for 128-row tiles");
+    static constexpr int NSTEP16 = C::KS / 4;
+    typedef Cfg<1, C::WO * C::WM, 1, C::TM / (C::WO * C::WM) / 16, C::KS, C::NS, C::VW,
+                (C::JB < NSTEP16 ? C::JB : NSTEP16 - 1), 16> type;      // 16 x TM
+    static_assert(type::TM == C::TM && type::TO == 16, "eight pieces stacked along the filters");
+};
+
 // Run piece `part` of the tile at (o0, m0) of the whole-tile shape C as shape P.
 template <class C, class P>
 __device__ __forceinline__ void conv_piece(const ConvParams& p, unsigned char* lds, int o0, int m0, int part)
@@ -653,7 +666,8 @@ __device__ __forceinline__ void conv_piece(const ConvParams& p, unsigned char* l
     conv_tile<P, C::TO * 4096 + C::TM>(p, lds, o0 + po * P::TO, m0 + pm * P::TM);     // one CONTEXT per parent shape
 }
 
-// SPLITS: 1 = whole tiles only; 2 = the kernel also carries the half-tile body; 4 = half and quarter.
+// SPLITS: 1 = whole tiles only; 2 = the kernel also carries the half-tile body; 4 = half and quarter;
+// 8 = half, quarter and the 16-row eighth.
 // THIRDS: it carries the 48-row body as well.
 template <class C, int SPLITS, bool THIRDS = false>
 __global__ void __launch_bounds__(C::NT) conv_fprop_kernel(const ConvParams p)
@@ -682,23 +696,36 @@ __global__ void __launch_bounds__(C::NT) conv_fprop_kernel(const ConvParams p)
         return;
     }
     if constexpr (SPLITS > 1) {
-        const ConvParams::PieceRegion& reg = bid < 0 ? p.front : p.back;
-        bid = bid < 0 ? (int)blockIdx.x : bid - whole;
-        int cls = 0;
-        if (bid >= 8 * reg.per_xcd[0]) {
-            bid -= 8 * reg.per_xcd[0];
-            cls = 1;
-            if (bid >= 8 * reg.per_xcd[1]) { bid -= 8 * reg.per_xcd[1];  cls = 2; }
-        }
-        const int j = (bid & 7) * reg.per_xcd[cls] + (bid >> 3);
-        if (j >= reg.count[cls]) return;                     // uniform per workgroup
-        const int q = reg.begin[cls] + j;                    // piece number within its class
+        // Scalar selects with constant indices only: a variable index, or a reference that may name
+        // either region, would move the argument block to scratch memory.
+        const bool in_front = bid < 0;
+        bid = in_front ? (int)blockIdx.x : bid - whole;
+        int cls = 0, per = 0, cnt = 0, beg = 0;
+        auto pick = [&](auto cc) {
+            constexpr int c = decltype(cc)::value;
+            per = in_front ? p.front.per_xcd[c] : p.back.per_xcd[c];
+            cnt = in_front ? p.front.count[c] : p.back.count[c];
+            beg = in_front ? p.front.begin[c] : p.back.begin[c];
+        };
+        pick(std::integral_constant<int, 0>{});
+        static_for<3>([&](auto cc) {
+            constexpr int c = decltype(cc)::value;
+            if (cls == c && bid >= 8 * per) {
+                bid -= 8 * per;
+                cls = c + 1;
+                pick(std::integral_constant<int, c + 1>{});
+            }
+        });
+        const int j = (bid & 7) * per + (bid >> 3);
+        if (j >= cnt) return;                                // uniform per workgroup
+        const int q = beg + j;                               // piece number within its class
         // The cut tiles follow the whole ones: first those cut in halves, then those cut in thirds,
-        // then those cut in quarters.
-        int cut = cls + 2, tile, part;
+        // in quarters, in eighths.
+        int cut = cls == 3 ? 8 : cls + 2, tile, part;
         if (cls == 0)      { tile = q >> 1;  part = q & 1; }
         else if (cls == 1) { tile = q / 3;   part = q - tile * 3;  tile += p.n_half; }
-        else               { tile = q >> 2;  part = q & 3;  tile += p.n_half + p.n_third; }
+        else if (cls == 2) { tile = q >> 2;  part = q & 3;  tile += p.n_half + p.n_third; }
+        else               { tile = q >> 3;  part = q & 7;  tile += p.n_half + p.n_third + p.n_quarter; }
         tile += p.n_whole;
         const int ms = tile / p.n_otiles;
         const int ot = tile - ms * p.n_otiles;
@@ -718,7 +745,13 @@ __global__ void __launch_bounds__(C::NT) conv_fprop_kernel(const ConvParams p)
             }
         }
         if constexpr (SPLITS >= 4) {
-            if (cut == 4) conv_piece<C, typename PieceOf<C, 4>::type>(p, lds_raw, o0, m0, part);
+            if (cut == 4) {
+                conv_piece<C, typename PieceOf<C, 4>::type>(p, lds_raw, o0, m0, part);
+                return;
+            }
+        }
+        if constexpr (SPLITS >= 8) {
+            if (cut == 8) conv_tile<typename EighthOf<C>::type, C::TO * 4096 + C::TM>(p, lds_raw, o0 + 16 * part, m0);
         }
     }
 }

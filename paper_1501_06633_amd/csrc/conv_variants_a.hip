@@ -13,7 +13,7 @@ namespace {
 typedef Cfg<2, 2, 2, 2, 16, 3, 4> C_o128m128;
 
 const VariantEntry kGroup[] = {
-    make_entry<C_o128m128, 4, true>("o128m128", 2, 0.900f, 0.900f),
+    make_entry<C_o128m128, 8, true>("o128m128", 2, 0.900f, 0.900f),
 };
 
 }  // namespace

@@ -13,7 +13,7 @@ typedef Cfg<2, 2, 2, 2, 8, 4, 4> C_o128m128k8;
 
 const VariantEntry kGroup[] = {
     // 32 KB ring + 20 KB table = 52 KB: three workgroups per CU whatever K is
-    make_entry<C_o128m128k8, 4>("o128m128k8", 3, 0.905f, 0.870f, 2560),
+    make_entry<C_o128m128k8, 8>("o128m128k8", 3, 0.905f, 0.870f, 2560),
 };
 
 }  // namespace

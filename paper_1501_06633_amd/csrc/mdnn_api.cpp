@@ -92,7 +92,8 @@ bool variant_usable(const mdnn::VariantInfo& v, int Nb, int No)
 // slot starts when the unit is nearly empty and runs alone, at about half the
 // matrix rate.  So the cut to take is the finest one that still leaves at most
 // one piece per unit:
-//   r <= 64 left-over tiles: quarters (1.25 tile times for the round instead of 2);
+//   r <= 32 left-over tiles: eighths of 16 rows (1.125), where measured to pay (see choose_cut());
+//   r <= 64: quarters (1.25 tile times for the round instead of 2);
 //   r <= 85: thirds (1.375; 338 tiles of 128 x 128 on a 13 x 13 layer: 80 -> 86 % of peak);
 //   r <= 128: halves (1.5);
 //   r <= 192: quarters in chains of up to three (a mixture that gives every unit a half or
@@ -102,26 +103,32 @@ bool variant_usable(const mdnn::VariantInfo& v, int Nb, int No)
 // each weighed by the piece's relative efficiency and taken only if it beats the coarser
 // choice by a margin.
 struct Cut {
-    int    n_whole, n_half, n_third, n_quarter;
+    int    n_whole, n_half, n_third, n_quarter, n_eighth;
     double cost;                       // of the partial round, in tile times (0 if there is none)
-    bool   pair_up;                    // a half and a quarter per unit: all pieces go in front of the whole tiles
-    int    pieces() const { return 2 * n_half + 3 * n_third + 4 * n_quarter; }
+    bool   pair_up;                    // a half and a smaller piece per unit: all pieces go in front of the whole tiles
+    int    pieces() const { return 2 * n_half + 3 * n_third + 4 * n_quarter + 8 * n_eighth; }
 };
 
-// `force`: 0 = choose; 'w' = no cutting; 'h', 't', 'q' = the left-over tiles in halves, thirds, quarters;
-// 'H', 'T', 'Q' = every tile so (tests and the block-size experiment pin a cut this way).  A kernel
-// that lacks the cut asked for returns n_whole = -1.
+// `force`: 0 = choose; 'w' = no cutting; 'h', 't', 'q', 'e' = the left-over tiles in halves, thirds,
+// quarters, eighths; 'H', 'T', 'Q', 'E' = every tile so; 'm', 'n' = 128 of the left-over tiles in halves
+// and the rest in quarters ('m') or eighths ('n'), all in front (tests and the block-size experiment
+// pin a cut this way).  A kernel that lacks the cut asked for returns n_whole = -1.
 Cut choose_cut(const mdnn::VariantInfo& v, int n_tiles, char force = 0)
 {
-    Cut c = {n_tiles, 0, 0, 0, 0.0, false};
+    Cut c = {n_tiles, 0, 0, 0, 0, 0.0, false};
     if (force) {
-        const bool all = force == 'H' || force == 'T' || force == 'Q';
+        const bool all = force == 'H' || force == 'T' || force == 'Q' || force == 'E';
         const int  n = all ? n_tiles : n_tiles % kComputeUnits;
         const char f = all ? (char)(force - 'A' + 'a') : force;
         const bool has = f == 'w' || (f == 'h' && v.max_split >= 2) || (f == 't' && v.thirds) || (f == 'q' && v.max_split >= 4) ||
-                         (f == 'm' && v.max_split >= 4 && n > 128 && n <= 192);
+                         (f == 'e' && v.max_split >= 8) || (f == 'm' && v.max_split >= 4 && n > 128 && n <= 192) ||
+                         (f == 'n' && v.max_split >= 8 && n > 128 && n <= 160) ||
+                         (f == 'p' && v.max_split >= 8 && n > 64 && n <= 96);
         if (!has) { c.n_whole = -1; return c; }
         if (f == 'm') { c.n_half = 128;  c.n_quarter = n - 128;  c.pair_up = true; }
+        if (f == 'n') { c.n_half = 128;  c.n_eighth = n - 128;  c.pair_up = true; }
+        if (f == 'p') { c.n_quarter = 64;  c.n_eighth = n - 64;  c.pair_up = true; }
+        if (f == 'e') c.n_eighth = n;
         if (f == 'h') c.n_half = n;
         if (f == 't') c.n_third = n;
         if (f == 'q') c.n_quarter = n;
@@ -133,11 +140,12 @@ Cut choose_cut(const mdnn::VariantInfo& v, int n_tiles, char force = 0)
     if (r == 0) return c;
     c.cost = 1.0;
     if (v.max_split < 2) return c;
-    const double e2 = 0.93, e3 = 0.90, e4 = 0.85;      // a half, a 48-row third, a quarter against a whole tile
+    const double e2 = 0.93, e3 = 0.90, e4 = 0.85, e8 = 0.70;   // a half, a 48-row third, a quarter, an eighth against a whole tile
     auto rounds_of = [&](int f) { return (double)((r * f + kComputeUnits - 1) / kComputeUnits) / f; };
-    auto take = [&](double cost, int nh, int nt, int nq) {
-        if (cost < c.cost - 0.05) { c.cost = cost;  c.n_half = nh;  c.n_third = nt;  c.n_quarter = nq; }
+    auto take = [&](double cost, int nh, int nt, int nq, int ne = 0, bool pair = false) {
+        if (cost < c.cost - 0.05) { c.cost = cost;  c.n_half = nh;  c.n_third = nt;  c.n_quarter = nq;  c.n_eighth = ne;  c.pair_up = pair; }
     };
+    const bool one_round = n_tiles > kComputeUnits && n_tiles < 2 * kComputeUnits;
     take(rounds_of(2) / e2, r, 0, 0);
     // Thirds only beside at most one round of whole tiles.  With two rounds on a kernel that holds
     // two workgroups per unit, piece and first whole tile end together, both slots of every unit
@@ -146,16 +154,31 @@ Cut choose_cut(const mdnn::VariantInfo& v, int n_tiles, char force = 0)
     // three-per-unit kernel).
     if (v.thirds && 3 * r <= kComputeUnits && n_tiles < 2 * kComputeUnits) take(0.375 / e3, 0, r, 0);
     if (v.max_split >= 4) take(rounds_of(4) / e4, 0, 0, r);
-    // One round of whole tiles plus 128 < r <= 192 on a kernel that holds three workgroups per unit:
-    // a half, a quarter and a whole tile per unit, all started together (pieces in front), end
-    // together after (128 + 64 + 32) / 128 tile times; quarter chains run their tail alone.  386 ... 446
-    // tiles: 125 us against 129 us for the best other choice.  Only with one round: with two or
-    // three, everything that starts together ends together and the dispatcher then packs the next
-    // round three to a unit on a third of the units (255 us against 194 us), with four or five the
-    // gain is under 1 %.
-    if (v.max_split >= 4 && v.est_wg_per_cu >= 3 && n_tiles > kComputeUnits && n_tiles < 2 * kComputeUnits && r > 128 && r <= 192 &&
-        0.75 < c.cost - 0.05) {
-        c.cost = 0.75;  c.n_half = 128;  c.n_third = 0;  c.n_quarter = r - 128;  c.pair_up = true;
+    // Eighths where they leave one 16-row piece per unit at most -- and only where every workgroup
+    // of the launch is resident from the start, so that nothing depends on where the dispatcher
+    // puts what comes later.  On the three-per-unit kernel that is beside exactly two rounds (540
+    // tiles: 90.7 % of peak against 86.3 % with quarters; beside one round the quarter is as fast;
+    // beside three or six rounds 71 % against 89.5 %: the whole tiles that do not fit at first land
+    // three to a unit).  On the two-per-unit kernel beside one round (280 tiles: 81.4 against
+    // 78.3 %; beside two: 81.9 against 84.9 %).
+    if (v.max_split >= 8 && 8 * r <= kComputeUnits && n_tiles / kComputeUnits == (v.est_wg_per_cu >= 3 ? 2 : 1))
+        take(0.125 / e8, 0, 0, 0, r);
+    // One round of whole tiles on a kernel that holds three workgroups per unit: a whole tile and
+    // two pieces per unit, all started together (pieces in front), end together; chains of equal
+    // pieces run their tail alone.
+    //   128 < r <= 192: a half and a quarter, (128 + 64 + 32) / 128 tile times (386 ... 446 tiles:
+    //       125 us against 129 us for the best other choice);
+    //   128 < r <= 160: a half and an eighth, (128 + 64 + 16) / 128 (392 tiles of a 14 x 14 layer
+    //       with 512 channels: 85.8 % of peak against 80.0 %; 406 tiles: 86.8 against 81.1 %);
+    //   85 < r <= 96: a quarter and an eighth, (128 + 32 + 16) / 128 (352 tiles: 87.4 % against
+    //       83.4 % with halves; up to 85 the 48-row thirds of the deep-slab kernel do as well).
+    // Only with one round: with two or three, everything that starts together ends together and
+    // the dispatcher then packs the next round three to a unit on a third of the units (255 us
+    // against 194 us), with four or five the gain is under 1 %.
+    if (v.max_split >= 4 && v.est_wg_per_cu >= 3 && one_round) {
+        if (v.max_split >= 8 && r > 128 && r <= 160) take(0.65, 128, 0, 0, r - 128, true);
+        else if (r > 128 && r <= 192)                take(0.75, 128, 0, r - 128, 0, true);
+        if (v.max_split >= 8 && r > 85 && r <= 96)   take(0.40, 0, 0, 64, r - 64, true);
     }
     if (c.pieces() > 0) c.n_whole = n_tiles - r;
     return c;
@@ -239,7 +262,7 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
     if (!variant || !variant[0] || std::strcmp(variant, "auto") == 0) {
         v = choose(Nb, No, g.M, g.K);
     } else {
-        // "name" or "name:c" with c one of w h t q H T Q (see choose_cut)
+        // "name" or "name:c" with c one of w h t q e m n H T Q E (see choose_cut)
         char name[32];
         const char* colon = std::strchr(variant, ':');
         const size_t len = colon ? (size_t)(colon - variant) : std::strlen(variant);
@@ -247,7 +270,7 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
         std::memcpy(name, variant, len);
         name[len] = 0;
         if (colon) {
-            if (!colon[1] || colon[2] || !std::strchr("whtqmHTQ", colon[1])) return MDNN_EINVAL;
+            if (!colon[1] || colon[2] || !std::strchr("whtqemnpHTQE", colon[1])) return MDNN_EINVAL;
             force_cut = colon[1];
         }
         v = find_variant(name);
@@ -274,7 +297,7 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
     const Cut cut = choose_cut(vi, p.n_tiles, force_cut);
     if (cut.n_whole < 0) return MDNN_EINVAL;                  // this kernel cannot cut a tile that way
     p.n_whole = cut.n_whole;
-    p.n_half = cut.n_half;  p.n_third = cut.n_third;  p.n_quarter = cut.n_quarter;
+    p.n_half = cut.n_half;  p.n_third = cut.n_third;  p.n_quarter = cut.n_quarter;  p.n_eighth = cut.n_eighth;
     p.n_pieces = cut.pieces();
     // Pieces go last, where the dispatcher deals them to whichever units free up first -- except
     // up to one per unit, which go FIRST.  A piece launched last runs alone on its unit, and a lone
@@ -284,17 +307,17 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
     // of tiles; -0.6 % with a single round of whole tiles, hence the condition).  The largest
     // pieces are the ones that go first.
     {
-        const int total[3] = {2 * p.n_half, 3 * p.n_third, 4 * p.n_quarter};
+        const int total[4] = {2 * p.n_half, 3 * p.n_third, 4 * p.n_quarter, 8 * p.n_eighth};
         int room = cut.pair_up ? 2 * kComputeUnits : p.n_whole >= 2 * kComputeUnits ? kComputeUnits : 0;
-        for (int c = 0; c < 3; ++c) {
+        for (int c = 0; c < 4; ++c) {
             const int f = std::min(total[c], room);
             room -= f;
             p.front.begin[c] = 0;         p.front.count[c] = f;            p.front.per_xcd[c] = div_up(f, 8);
             p.back.begin[c] = f;          p.back.count[c] = total[c] - f;  p.back.per_xcd[c] = div_up(total[c] - f, 8);
         }
         for (mdnn::ConvParams::PieceRegion* r : {&p.front, &p.back}) {
-            r->wgs = 8 * (r->per_xcd[0] + r->per_xcd[1] + r->per_xcd[2]);
-            r->pieces = r->count[0] + r->count[1] + r->count[2];
+            r->wgs = 8 * (r->per_xcd[0] + r->per_xcd[1] + r->per_xcd[2] + r->per_xcd[3]);
+            r->pieces = r->count[0] + r->count[1] + r->count[2] + r->count[3];
         }
     }
     p.tiles_per_xcd = div_up(p.n_whole, 8);
@@ -405,13 +428,13 @@ mdnn_status mdnn_describe_launch(int Nb, int Wi, int Hi, int Nc, int No, int Sk,
     const mdnn::VariantInfo& vi = mdnn::variant_info(v);
     std::snprintf(text, text_size,
                   "variant=%s tile=%dx%d kslab=%d threads=%d K=%d M=%d tiles=%d whole=%d split=%d "
-                  "halved=%d thirded=%d quartered=%d pieces=%d "
+                  "halved=%d thirded=%d quartered=%d eighthed=%d pieces=%d "
                   "pieces_first=%d grid=%d lds_bytes=%u table_entries=%d",
                   vi.name, vi.tile_o, vi.tile_m, vi.kslab, vi.threads, p.K, p.M, p.n_tiles, p.n_whole,
                   // split: pieces per cut tile when all are cut alike (1 = none is cut), 0 = a mixture
-                  p.n_pieces == 0 ? 1 : (p.n_third == 0 && p.n_quarter == 0) ? 2 : (p.n_half == 0 && p.n_quarter == 0) ? 3
-                                    : (p.n_half == 0 && p.n_third == 0) ? 4 : 0,
-                  p.n_half, p.n_third, p.n_quarter, p.n_pieces, p.front.pieces,
+                  p.n_pieces == 0 ? 1 : p.n_pieces == 2 * p.n_half ? 2 : p.n_pieces == 3 * p.n_third ? 3
+                                    : p.n_pieces == 4 * p.n_quarter ? 4 : p.n_pieces == 8 * p.n_eighth ? 8 : 0,
+                  p.n_half, p.n_third, p.n_quarter, p.n_eighth, p.n_pieces, p.front.pieces,
                   p.front.wgs + 8 * p.tiles_per_xcd + p.back.wgs,
                   mdnn::variant_lds_bytes(v, p.tab_cap), p.tab_cap);
     return MDNN_OK;

@@ -32,18 +32,18 @@ struct ConvParams {
     // thirds (48 + 48 + 32 filter rows of a 128-row tile), then n_quarter tiles in quarters.
     // Pieces are numbered within their class (halves, pieces of thirded tiles, quarters).
     int n_whole;
-    int n_half, n_third, n_quarter;
-    int n_pieces;        // 2 n_half + 3 n_third + 4 n_quarter
+    int n_half, n_third, n_quarter, n_eighth;
+    int n_pieces;        // 2 n_half + 3 n_third + 4 n_quarter + 8 n_eighth
     int tiles_per_xcd;   // ceil(n_whole / 8)
     // Launch order: the `front` pieces, the whole tiles, the `back` pieces.  Within a region the
     // classes follow each other, largest pieces first, and every class is dealt to the 8 XCDs in
     // contiguous runs of per_xcd pieces (so every XCD gets its share of every size).
     struct PieceRegion {
-        int begin[3];    // first piece of class c (0 halves, 1 thirds, 2 quarters) in this region
-        int count[3];    // pieces of class c in this region
-        int per_xcd[3];  // ceil(count / 8)
-        int wgs;         // 8 * (per_xcd[0] + per_xcd[1] + per_xcd[2]): workgroups the region occupies in the grid
-        int pieces;      // count[0] + count[1] + count[2]
+        int begin[4];    // first piece of class c (0 halves, 1 thirds, 2 quarters, 3 eighths) in this region
+        int count[4];    // pieces of class c in this region
+        int per_xcd[4];  // ceil(count / 8)
+        int wgs;         // 8 * (sum of per_xcd): workgroups the region occupies in the grid
+        int pieces;      // sum of count
     };
     PieceRegion front, back;
     // Column-tile order.  When a tile covers whole output pixels and a row of pixels is a whole
@@ -78,7 +78,7 @@ struct VariantInfo {
     float eff;           // sustained fraction of the matrix rate with many tiles per compute unit (measured)
     float eff_few;       // same with fewer than four tiles per compute unit: start-up and drain of
                          // co-resident workgroups coincide instead of overlapping (measured)
-    int max_split;       // 1, 2 or 4: finest even cut of a tile this variant's kernel can run
+    int max_split;       // 1, 2, 4 or 8: finest even cut of a tile this variant's kernel can run
     int thirds;          // 1: the kernel can also run a tile as 48 + 48 + 32 filter rows
     int max_tab;         // most offset-table entries kept in LDS at once (longer K: several fills per tile)
 };

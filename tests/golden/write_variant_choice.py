@@ -36,7 +36,7 @@ def shapes():
 def line(name, dims):
     d = B.mdnn_describe_launch(*dims)
     return (f"{name} {' '.join(map(str, dims))} {d['variant']} tiles={d['tiles']} whole={d['whole']} "
-            f"halved={d['halved']} thirded={d['thirded']} quartered={d['quartered']} first={d['pieces_first']}")
+            f"halved={d['halved']} thirded={d['thirded']} quartered={d['quartered']} eighthed={d['eighthed']} first={d['pieces_first']}")
 
 
 def text():

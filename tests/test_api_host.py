@@ -182,8 +182,8 @@ def test_describe_launch(L):
     assert d["variant"] in B.mdnn_variant_names()
     to, tm = map(int, d["tile"].split("x"))
     assert d["tiles"] == -(-256 // to) * -(-d["M"] // tm)
-    assert d["whole"] + d["halved"] + d["thirded"] + d["quartered"] == d["tiles"]
-    assert d["pieces"] == 2 * d["halved"] + 3 * d["thirded"] + 4 * d["quartered"]
+    assert d["whole"] + d["halved"] + d["thirded"] + d["quartered"] + d["eighthed"] == d["tiles"]
+    assert d["pieces"] == 2 * d["halved"] + 3 * d["thirded"] + 4 * d["quartered"] + 8 * d["eighthed"]
     assert d["lds_bytes"] <= 160 * 1024 and d["table_entries"] % d["kslab"] == 0
     # a pinned variant, a plan with the tail cut in pieces, and the error paths
     d = B.mdnn_describe_launch(128, 91, 6, 8, 128, 3, 1, 0, "o128m128")
@@ -196,13 +196,16 @@ def test_describe_launch(L):
 
 def test_how_the_last_round_is_cut(L):
     """128 images, 128 filters, 3x3 unpadded: Ho * Wo tiles of 128x128.  What becomes of the
-    r = tiles mod 256 left-over tiles: quarters up to 64, thirds (48 + 48 + 32 rows; the deep-slab
-    kernel only) up to 85, halves up to 128, quarters (up to three per unit) up to 192, then
-    whole tiles."""
+    r = tiles mod 256 left-over tiles: eighths up to 32 (where measured to pay), quarters up to 64,
+    thirds (48 + 48 + 32 rows; the deep-slab kernel only) up to 85, halves up to 128, quarters (up
+    to three per unit) up to 192, then whole tiles; beside a single round the three-per-unit
+    kernel gives every unit a whole tile and two pieces of different heights."""
     def cut(r, variant):
         d = B.mdnn_describe_launch(128, 2 + 16, 2 + (16 + r // 16), 4, 128, 3, 1, 0, variant) if r % 16 == 0 else \
             B.mdnn_describe_launch(128, 2 + 1, 2 + (256 + r), 4, 128, 3, 1, 0, variant)
-        assert d["tiles"] == 256 + r and d["whole"] + d["halved"] + d["thirded"] + d["quartered"] == d["tiles"]
+        assert d["tiles"] == 256 + r and d["whole"] + d["halved"] + d["thirded"] + d["quartered"] + d["eighthed"] == d["tiles"]
+        if d["eighthed"]:
+            return d["split"], d["halved"], d["thirded"], d["quartered"], d["eighthed"]
         return d["split"], d["halved"], d["thirded"], d["quartered"]
     for v in ("o128m128", "o128m128k8"):
         assert cut(0, v) == (1, 0, 0, 0)
@@ -214,14 +217,26 @@ def test_how_the_last_round_is_cut(L):
     assert cut(65, "o128m128") == (3, 0, 65, 0) and cut(82, "o128m128") == (3, 0, 82, 0)
     assert cut(85, "o128m128") == (3, 0, 85, 0) and cut(86, "o128m128") == (2, 86, 0, 0)
     assert cut(82, "o128m128k8") == (2, 82, 0, 0)
+    # eighths: beside one round on the two-per-unit kernel, beside exactly two on the three-per-unit one
+    assert cut(24, "o128m128") == (8, 0, 0, 0, 24) and cut(32, "o128m128") == (8, 0, 0, 0, 32) and cut(33, "o128m128") == (4, 0, 0, 33)
+    assert cut(24, "o128m128k8") == (4, 0, 0, 24)
+    d = B.mdnn_describe_launch(128, 2 + 1, 2 + 540, 4, 128, 3, 1, 0, "o128m128k8")
+    assert (d["whole"], d["split"], d["eighthed"], d["pieces"], d["pieces_first"]) == (512, 8, 28, 224, 224)
+    d = B.mdnn_describe_launch(128, 2 + 1, 2 + 540, 4, 128, 3, 1, 0, "o128m128")
+    assert (d["whole"], d["split"], d["quartered"]) == (512, 4, 28)
+    d = B.mdnn_describe_launch(128, 2 + 1, 2 + 800, 4, 128, 3, 1, 0, "o128m128k8")
+    assert (d["whole"], d["split"], d["quartered"]) == (768, 4, 32)
     # thirds only beside at most one round of whole tiles: 512 + 76 tiles are halved
     d = B.mdnn_describe_launch(128, 2 + 1, 2 + 588, 4, 128, 3, 1, 0, "o128m128")
     assert (d["tiles"], d["whole"], d["split"], d["halved"]) == (588, 512, 2, 76)
-    # beside a single round, the three-per-unit kernel pairs a half with a quarter on every unit
-    assert cut(136, "o128m128") == (4, 0, 0, 136) and cut(136, "o128m128k8") == (0, 128, 0, 8)
-    assert cut(192, "o128m128k8") == (0, 128, 0, 64) and cut(129, "o128m128k8") == (0, 128, 0, 1)
+    # beside a single round, the three-per-unit kernel gives every unit two pieces: a half with an
+    # eighth (to 160) or a quarter (to 192), a quarter with an eighth (86 ... 96)
+    assert cut(136, "o128m128") == (4, 0, 0, 136) and cut(136, "o128m128k8") == (0, 128, 0, 0, 8)
+    assert cut(160, "o128m128k8") == (0, 128, 0, 0, 32) and cut(161, "o128m128k8") == (0, 128, 0, 33)
+    assert cut(192, "o128m128k8") == (0, 128, 0, 64) and cut(129, "o128m128k8") == (0, 128, 0, 0, 1)
+    assert cut(86, "o128m128k8") == (0, 0, 0, 64, 22) and cut(96, "o128m128k8") == (0, 0, 0, 64, 32) and cut(97, "o128m128k8") == (2, 97, 0, 0)
     d = B.mdnn_describe_launch(128, 2 + 1, 2 + 392, 4, 128, 3, 1, 0, "o128m128k8")
-    assert (d["whole"], d["pieces"], d["pieces_first"]) == (256, 288, 288)          # all pieces in front
+    assert (d["whole"], d["pieces"], d["pieces_first"]) == (256, 320, 320)          # all pieces in front
     d = B.mdnn_describe_launch(128, 2 + 1, 2 + 648, 4, 128, 3, 1, 0, "o128m128k8")   # two rounds + 136: quarters
     assert (d["whole"], d["split"], d["quartered"]) == (512, 4, 136)
     d = B.mdnn_describe_launch(128, 2 + 1, 2 + 136, 4, 128, 3, 1, 0, "o128m128k8")   # no whole round at all

@@ -31,7 +31,7 @@ DRIVER = textwrap.dedent(r"""
         if (mdnn_out_dims(Wi, Hi, Sk, s, p, &Wo, &Ho) == MDNN_OK) (void)mdnn_conv_flops(Nb, Wo, Ho, Nc, No, Sk);
         (void)mdnn_choose_variant(Nb, Wi, Hi, Nc, No, Sk, s, p);
         if (mdnn_describe_launch(Nb, Wi, Hi, Nc, No, Sk, s, p, nullptr, text, sizeof text) == MDNN_OK) ok++;
-        const char cuts[] = "whtqHTQ";
+        const char cuts[] = "whtqemnpHTQE";
         for (int v = 0; v < mdnn_variant_count(); ++v) {
             char name[48];
             (void)mdnn_describe_launch(Nb, Wi, Hi, Nc, No, Sk, s, p, mdnn_variant_name(v), text, sizeof text);

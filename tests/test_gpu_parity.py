@@ -232,16 +232,19 @@ def test_mid_size_all_variants_integer_bitwise(env):
         np.testing.assert_array_equal(got, want, err_msg=variant)
 
 
-# ------------------------------------------------- tail pieces (half / third / quarter tiles)
+# ------------------------------------------------- tail pieces (half / third / quarter / eighth tiles)
 TAILS = [
     # name        Nb  Hi  Wi  Nc  No  Sk st pad alpha  pieces per cut tile with the deep-slab kernel, with the shallow-slab one
     ("halves",    128,  6, 91,  8, 128, 3, 1, 0, 1.0,  2, 2),      # 356 tiles: 100 left over -> halves
     ("quarters",  128, 10, 39,  8, 128, 3, 1, 0, 0.5,  4, 4),      # 296 tiles:  40 left over -> quarters
-    ("quarters_ragged", 64, 11, 40, 6, 200, 3, 1, 1, 2.0, 4, (128, 0, 56)),   # padded, ragged filter tile, 2 pixels per tile; 440 tiles
+    ("quarters_ragged", 64, 11, 40, 6, 200, 3, 1, 1, 2.0, 4, (128, 0, 56, 0)),   # padded, ragged filter tile, 2 pixels per tile; 440 tiles
     ("thirds",    128, 14, 30,  8, 128, 3, 1, 0, 1.0,  3, 2),      # 336 tiles: 80 left over -> 48 + 48 + 32 rows
     ("thirds_ragged", 64, 12, 28, 6, 200, 3, 1, 1, 2.0, 3, 2),     # 336 tiles, the second filter tile has 72 rows
-    # 392 tiles, 136 left over: up to three quarters per unit; the three-per-unit kernel pairs halves with quarters
-    ("one_round_136", 128, 16, 30, 8, 128, 3, 1, 0, 0.5, 4, (128, 0, 8)),
+    # 392 tiles, 136 left over: up to three quarters per unit; the three-per-unit kernel pairs halves with eighths
+    ("one_round_136", 128, 16, 30, 8, 128, 3, 1, 0, 0.5, 4, (128, 0, 0, 8)),
+    ("one_round_89", 128, 17, 25, 8, 128, 3, 1, 0, 0.5, 2, (0, 0, 64, 25)),   # 345 tiles: halves; quarters paired with eighths
+    ("one_round_24", 128, 12, 30, 8, 128, 3, 1, 0, 2.0, 8, 4),                 # 280 tiles: eighths beside one round on the deep-slab kernel
+    ("two_rounds_28", 128, 22, 29, 8, 128, 3, 1, 0, 1.0, 4, 8),                # 540 tiles: eighths beside two rounds on the shallow-slab kernel
     ("two_rounds_136", 128, 20, 38, 8, 128, 3, 1, 0, 0.5, 4, 4),    # 648 tiles: quarter chains on both
 ]
 
@@ -249,15 +252,15 @@ TAILS = [
 @pytest.mark.parametrize("case", TAILS, ids=[c[0] for c in TAILS])
 @pytest.mark.parametrize("variant", ["o128m128", "o128m128k8"])
 def test_tail_pieces_bitwise(env, case, variant):
-    """Launches whose last partial round of tiles is cut into half, third or quarter
-    tiles: the plan says so, and integer data must match the oracle bit for bit."""
+    """Launches whose last partial round of tiles is cut into half, third, quarter or
+    eighth tiles: the plan says so, and integer data must match the oracle bit for bit."""
     _, B, oracle = env
     name, Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha, want_deep, want_shallow = case
     want = want_deep if variant == "o128m128" else want_shallow
     plan = B.mdnn_describe_launch(Nb, Wi, Hi, Nc, No, Sk, stride, pad, variant)
     say(f"[parity-tail] case={name} variant={variant} plan={plan}")
-    if isinstance(want, tuple):          # (halved, thirded, quartered): a mixture, all of it in front of the whole tiles
-        assert plan["split"] == 0 and (plan["halved"], plan["thirded"], plan["quartered"]) == want
+    if isinstance(want, tuple):          # (halved, thirded, quartered, eighthed): a mixture, all of it in front of the whole tiles
+        assert plan["split"] == 0 and (plan["halved"], plan["thirded"], plan["quartered"], plan["eighthed"]) == want
         assert sum(want) == plan["tiles"] - plan["whole"] and plan["pieces_first"] == plan["pieces"]
     else:
         assert plan["split"] == want and plan["pieces"] == (plan["tiles"] - plan["whole"]) * want
@@ -290,6 +293,10 @@ def test_tail_pieces_along_the_columns_bitwise(env):
     ("o128m128:T", 256, dict(tiles=182, whole=0, split=3, thirded=182, pieces=546, pieces_first=0)),
     # thirds of the last round with two rounds of whole tiles in front: the pieces go first
     ("o128m128:t", 1664, dict(tiles=1183, whole=1024, split=3, thirded=159, pieces=477, pieces_first=256)),
+    # every tile in eighths (16-row pieces only), on both kernels; eighths in front of and behind four rounds
+    ("o128m128:E", 256, dict(tiles=182, whole=0, split=8, eighthed=182, pieces=1456, pieces_first=0)),
+    ("o128m128k8:E", 256, dict(tiles=182, whole=0, split=8, eighthed=182, pieces=1456, pieces_first=0)),
+    ("o128m128k8:e", 1664, dict(tiles=1183, whole=1024, split=8, eighthed=159, pieces=1272, pieces_first=256)),
 ])
 def test_pieces_before_and_after_the_whole_tiles_bitwise(env, variant, No, want_plan):
     """With two or more rounds of whole tiles, up to one piece per CU is launched before them and

@@ -81,16 +81,17 @@ def test_long_contractions_every_variant_bitwise():
 
 def test_pinned_cuts_on_random_shapes_bitwise():
     """Thirty seeded mid-size shapes whose tiles are all cut, or whose last round is cut, in every way
-    a kernel offers (halves, 48 + 48 + 32-row thirds, quarters; pinned through the variant name):
+    a kernel offers (halves, 48 + 48 + 32-row thirds, quarters, 16-row eighths, pairings of two sizes;
+    pinned through the variant name):
     ragged filter counts, ragged column counts, pads and strides, integer data, bit for bit."""
     import torch
     from paper_1501_06633_amd import binding as B
     import oracle
 
     pinned = ["o128m128:H", "o128m128:T", "o128m128:Q", "o128m128:t", "o128m128k8:H", "o128m128k8:Q",
-              "o96m256:H", "o96m256:h", "o128m128k8:m", "o64m256k8:H", "o64m256k8:Q", "o64m256k8:q", "o48m128:w", "o64m512:w"]
+              "o96m256:H", "o96m256:h", "o128m128k8:m", "o128m128k8:n", "o128m128k8:p", "o128m128k8:E", "o128m128:e", "o64m256k8:H", "o64m256k8:Q", "o64m256k8:q", "o48m128:w", "o64m512:w"]
     rng = np.random.default_rng(4096)
-    runs = 0
+    runs = paired = 0
     for it in range(30):
         Nb = int(rng.choice([4, 8, 16, 32, 64]))
         Sk = int(rng.choice([1, 3, 3, 5]))
@@ -108,13 +109,15 @@ def test_pinned_cuts_on_random_shapes_bitwise():
         what = f"case={it} Nb={Nb} Hi={Hi} Wi={Wi} Nc={Nc} No={No} Sk={Sk} stride={stride} pad={pad} alpha={alpha}"
         print(what, flush=True)
         for v in pinned:
-            if v.endswith(":m"):          # the half + quarter pairing exists for 129 ... 192 left-over tiles only
+            pairing = {"m": (128, 192), "n": (128, 160), "p": (64, 96)}.get(v[-1]) if ":" in v else None
+            if pairing:                   # a pairing of two piece sizes exists for a range of left-over tiles only
                 r = B.mdnn_describe_launch(Nb, Wi, Hi, Nc, No, Sk, stride, pad, v.split(":")[0])["tiles"] % 256
-                if not 128 < r <= 192:
+                if not pairing[0] < r <= pairing[1]:
                     runs += 1
                     continue
+                paired += 1
             y = B.mdnn_conv_fprop(d_x, d_w, stride, pad, alpha, variant=v)
             torch.cuda.synchronize()
             np.testing.assert_array_equal(y.cpu().numpy(), want, err_msg=f"{what} variant={v}")
             runs += 1
-    assert runs == 30 * len(pinned)
+    assert runs == 30 * len(pinned) and paired >= 3
