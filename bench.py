@@ -352,7 +352,7 @@ def main():
     if args.block_sizes:
         rows = {}
         for v in B.mdnn_variant_names():
-            if v.endswith("s"):
+            if v[-1] in "sab":                               # 4-byte copies of one or both operands
                 continue
             r, _ = layer_report(torch, B, W, args.workload, 30, 5, v, min_warm_ms=WARM_MS_FLOOR)
             plan = B.mdnn_describe_launch(L.Nb, L.Wi, L.Hi, L.Nc, L.No, L.Sk, L.stride, L.pad, v)
@@ -546,7 +546,7 @@ def main():
                     auto = B.mdnn_choose_variant(nb, hw, hw, nc, no, 3, 1, 1)
                     res = {}
                     for v in B.mdnn_variant_names():
-                        if v.endswith("s") or v == "o64m512":            # 4-byte copies; the output-bound tile
+                        if v[-1] in "sab" or v == "o64m512":             # 4-byte copies; the output-bound tile
                             continue
                         fn = lambda: B.mdnn_conv_fprop(d_in, d_f, 1, 1, 1.0, out=out, variant=v)
                         w = timed(fn, 3)

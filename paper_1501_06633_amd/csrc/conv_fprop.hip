@@ -40,7 +40,8 @@ const std::vector<VariantEntry>& entries()
     static const std::vector<VariantEntry> all = [] {
         std::vector<VariantEntry> v;
         const VariantEntry* (*const groups[])(int*) = {conv_variants_a, conv_variants_b, conv_variants_c, conv_variants_d,
-                                                       conv_variants_e, conv_variants_f, conv_variants_g};
+                                                       conv_variants_e, conv_variants_f, conv_variants_g,
+                                                       conv_variants_h};
         for (auto g : groups) {
             int n = 0;
             const VariantEntry* e = g(&n);

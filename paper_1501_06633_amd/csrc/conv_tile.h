@@ -74,7 +74,9 @@ template <class V> __device__ __forceinline__ float comp(const V& v, int i)
 // (MB = 32: v_mfma_f32_32x32x2_f32, two k per instruction; MB = 16:
 // v_mfma_f32_16x16x4_f32, four k per instruction -- the same FLOPs per cycle,
 // half the block edge, which is what tile heights of 48 rows need); KS patch
-// columns per slab; NS LDS stages; VW floats per global access (4 or 1).
+// columns per slab; NS LDS stages; VW floats per global access: 4 or 1 for both
+// operands, 14 = 4-byte filter copies and 16-byte patch copies (a filter count
+// that is no multiple of 4), 41 = the other way round (such a minibatch).
 template <int WO_, int WM_, int RA_, int RB_, int KS_, int NS_, int VW_, int JB_ = 2, int MB_ = 32>
 struct Cfg {
     static constexpr int WO = WO_, WM = WM_, RA = RA_, RB = RB_, KS = KS_, NS = NS_, VW = VW_;
@@ -84,10 +86,12 @@ struct Cfg {
     static constexpr int NT = 64 * WO * WM;           // threads
     static constexpr int TO = WO * RA * MB;           // tile rows (filters)
     static constexpr int TM = WM * RB * MB;           // tile columns (flat m)
-    static constexpr int OG = TO / VW;                // accesses per filter-slab row
+    static constexpr int VWA = (VW == 4 || VW == 41) ? 4 : 1;   // floats per filter copy
+    static constexpr int VWB = (VW == 4 || VW == 14) ? 4 : 1;   // floats per patch copy (and whether M is a multiple of 4)
+    static constexpr int OG = TO / VWA;               // accesses per filter-slab row
     static constexpr int A_EL = KS * OG;              // accesses per filter slab
     static constexpr int NA = (A_EL + NT - 1) / NT;   // filter accesses per thread per slab
-    static constexpr int MG = TM / VW;                // accesses per patch-slab row
+    static constexpr int MG = TM / VWB;               // accesses per patch-slab row
     static constexpr int BROWS = NT / MG;             // patch rows one pass of the workgroup covers
     static constexpr int NB = KS / BROWS;             // patch accesses per thread per slab
     // global -> LDS copies every wave issues per slab (waves past the end of a
@@ -97,7 +101,7 @@ struct Cfg {
     static constexpr int NL = A_EL / NT + NB;
     static constexpr int STAGE_FLOATS = KS * (TO + TM);
     static constexpr uint32_t ring_bytes = (uint32_t)NS * STAGE_FLOATS * sizeof(float);
-    static_assert(VW == 1 || VW == 4, "VW");
+    static_assert(VW == 1 || VW == 4 || VW == 14 || VW == 41, "VW");
     static_assert(MB == 32 || MB == 16, "MB");
     static_assert(NT % MG == 0 && KS % BROWS == 0 && KS % KB == 0, "tile shape");
     static_assert(A_EL % 32 == 0, "the filter copy masks off whole waves and, in the last wave that copies, the upper lanes");
@@ -114,14 +118,14 @@ struct Cfg {
 template <class C, int CONTEXT = 0>
 __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* lds, const int o0, const int m0)
 {
-    constexpr int WO = C::WO, RA = C::RA, RB = C::RB, KS = C::KS, NS = C::NS, VW = C::VW;
+    constexpr int WO = C::WO, RA = C::RA, RB = C::RB, KS = C::KS, NS = C::NS, VWA = C::VWA, VWB = C::VWB;
     constexpr int MB = C::MB, KB = C::KB;
     constexpr int NV = MB * MB / 64;  // accumulator registers per matrix block
     typedef typename std::conditional<MB == 32, f32x16, f32x4>::type Acc;
     constexpr int NT = C::NT, TO = C::TO, TM = C::TM, OG = C::OG, MG = C::MG;
     constexpr int NA = C::NA, NB = C::NB, BROWS = C::BROWS, NL = C::NL;
     constexpr int STAGE_BYTES = C::STAGE_FLOATS * 4;
-    constexpr int ACCESS = 4 * VW;    // bytes per lane per global -> LDS copy
+    constexpr int ACCESS_A = 4 * VWA, ACCESS_B = 4 * VWB;    // bytes per lane per global -> LDS copy
     typedef typename VecOf<RB>::type BVec;
 
     u32x2* tab = reinterpret_cast<u32x2*>(lds + C::ring_bytes);   // [tab_cap] {byte offset, tap id}
@@ -149,7 +153,7 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
     int       iy0, ix0;               // image row/col of tap (0,0); far negative when the column is past M
     bool      col_inside;             // every tap of this column's patch lies inside the image
     {
-        const int m = m0 + VW * q;
+        const int m = m0 + VWB * q;
         if (m < p.M) {
             const int pix = (int)fast_div((uint32_t)m, p.nb_magic, p.nb_shift);
             const int n   = m - pix * p.Nb;
@@ -207,10 +211,11 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
         const int e = t + i * NT;
         const int r = e / OG;
         const int c = e - r * OG;
-        voffA[i] = ((uint32_t)r * (uint32_t)p.No + (uint32_t)(o0 + VW * c)) * 4u;
+        voffA[i] = ((uint32_t)r * (uint32_t)p.No + (uint32_t)(o0 + VWA * c)) * 4u;
     }
     const uint32_t strideA = (uint32_t)KS * (uint32_t)p.No * 4u;
-    unsigned char* const dma_base = lds + wave * (64 * ACCESS);               // wave-uniform
+    unsigned char* const dma_base_a = lds + wave * (64 * ACCESS_A);           // wave-uniform
+    unsigned char* const dma_base_b = lds + wave * (64 * ACCESS_B);
     auto issue_A = [&](auto stc) {
         constexpr int st = decltype(stc)::value;
 #pragma unroll
@@ -218,7 +223,7 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
             if ((C::A_EL % NT) != 0 && wave * 64 + i * NT >= C::A_EL) continue;   // wave-uniform
             if (C::A_EL % 64 != 0 && wave * 64 + i * NT + lane >= C::A_EL) continue;   // last wave of the slab: lower lanes only
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rfl, LDS_PTR(dma_base + (st * STAGE_BYTES + i * NT * ACCESS)), C::VW * 4,
+                rfl, LDS_PTR(dma_base_a + (st * STAGE_BYTES + i * NT * ACCESS_A)), C::VWA * 4,
                 (int)voffA[i], 0, 0, 0);
             voffA[i] += strideA;
         }
@@ -243,7 +248,7 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
                 off = ok ? off : kOutOfRange;
             }
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rin, LDS_PTR(dma_base + (st * STAGE_BYTES + KS * TO * 4 + i * NT * ACCESS)), C::VW * 4,
+                rin, LDS_PTR(dma_base_b + (st * STAGE_BYTES + KS * TO * 4 + i * NT * ACCESS_B)), C::VWB * 4,
                 (int)off, 0, 0, 0);
         }
     };
@@ -491,7 +496,7 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
         }
         __syncthreads();
         // this lane's columns: with 16-byte copies its RB columns are images of one pixel
-        constexpr int NCOL = (VW == 4) ? 1 : RB;
+        constexpr int NCOL = (VWB == 4) ? 1 : RB;
         int  cy[NCOL], cx[NCOL], cn[NCOL];
         bool cok[NCOL];
 #pragma unroll
@@ -519,7 +524,7 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
                     // fewer than 2^30 elements: 32-bit index arithmetic cannot wrap
                     const uint32_t e = (((uint32_t)c * (uint32_t)p.scat_Hi + (uint32_t)iy) * (uint32_t)p.scat_Wi + (uint32_t)ix) *
                                            (uint32_t)p.Nb + (uint32_t)cn[b];
-                    if constexpr (VW == 4) {
+                    if constexpr (VWB == 4) {
                         BVec w;
 #pragma unroll
                         for (int bb = 0; bb < RB; ++bb) {
@@ -581,7 +586,7 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
             const int o = o_wave + block_row(a, v) + 4 * kg;
             if (o >= p.No) continue;
             float* dst = p.out + (size_t)o * (size_t)p.M + ocol;
-            if constexpr (VW == 4) {
+            if constexpr (VWB == 4) {
                 if (ocol < p.M) {                 // M % 4 == 0 and RB | 4: all or nothing
                     BVec w;
 #pragma unroll
@@ -761,7 +766,7 @@ template <class C, int SPLITS = 1, bool THIRDS = false>
 constexpr VariantEntry make_entry(const char* name, int wg_per_cu, float eff, float eff_few,
                                   int max_tab = kMaxTabEntries)
 {
-    return VariantEntry{VariantInfo{name, C::TO, C::TM, C::KS, C::NT, C::VW == 4 ? 1 : 0, wg_per_cu, eff, eff_few,
+    return VariantEntry{VariantInfo{name, C::TO, C::TM, C::KS, C::NT, C::VWA == 4 ? 1 : 0, C::VWB == 4 ? 1 : 0, wg_per_cu, eff, eff_few,
                                     SPLITS, THIRDS ? 1 : 0, max_tab},
                         &conv_fprop_kernel<C, SPLITS, THIRDS>, C::ring_bytes};
 }

@@ -77,7 +77,7 @@ void division_magic(uint32_t d, uint32_t* magic, uint32_t* shift)
 
 bool variant_usable(const mdnn::VariantInfo& v, int Nb, int No)
 {
-    return !v.vec || (Nb % 4 == 0 && No % 4 == 0);
+    return (!v.vec_a || No % 4 == 0) && (!v.vec_b || Nb % 4 == 0);
 }
 
 // Tail balancing.  With T tiles on 256 compute units the last T mod 256 tiles form
@@ -236,7 +236,8 @@ int choose(int Nb, int No, int64_t M, int64_t K)
     for (int i = 0; i < mdnn::variant_count(); ++i) {
         const mdnn::VariantInfo& v = mdnn::variant_info(i);
         if (!variant_usable(v, Nb, No)) continue;
-        if (!v.vec && Nb % 4 == 0 && No % 4 == 0) continue;      // 4-byte copies only where 16-byte ones cannot be used
+        // 4-byte copies only for the operand that cannot be copied 16 bytes at a time
+        if ((!v.vec_a && No % 4 == 0) || (!v.vec_b && Nb % 4 == 0)) continue;
         const double c = variant_cost(v, No, M);
         if (best < 0 || c < best_cost) { best = i; best_cost = c; }
     }

@@ -73,7 +73,8 @@ struct VariantInfo {
     int tile_m;          // flat (coordinate, batch) columns per workgroup tile
     int kslab;           // patch columns (k) staged in LDS per pipeline step
     int threads;         // workgroup size
-    int vec;             // 1: 16-byte loads/stores, needs Nb % 4 == 0 and No % 4 == 0
+    int vec_a;           // 1: 16-byte filter copies, needs No % 4 == 0
+    int vec_b;           // 1: 16-byte patch copies and stores, needs Nb % 4 == 0
     int est_wg_per_cu;   // workgroups expected to be co-resident on one compute unit
     float eff;           // sustained fraction of the matrix rate with many tiles per compute unit (measured)
     float eff_few;       // same with fewer than four tiles per compute unit: start-up and drain of
@@ -98,6 +99,7 @@ const VariantEntry* conv_variants_d(int* count);
 const VariantEntry* conv_variants_e(int* count);
 const VariantEntry* conv_variants_f(int* count);
 const VariantEntry* conv_variants_g(int* count);
+const VariantEntry* conv_variants_h(int* count);
 
 int                variant_count();
 const VariantInfo& variant_info(int i);

@@ -109,8 +109,10 @@ def test_misaligned(L):
 
 def test_unknown_or_unusable_variant(L):
     assert call(variant="no_such_tile") == B.MDNN_EINVAL
-    vec = [n for n in B.mdnn_variant_names() if not n.endswith("s")]
+    vec = [n for n in B.mdnn_variant_names() if n[-1] not in "sab"]
     assert call(variant=vec[0], Nb=6) == B.MDNN_EINVAL       # 16-byte variant needs Nb % 4 == 0
+    # the tiles with one narrow operand: "a" copies filters 4 bytes at a time (any No), "b" patches (any Nb)
+    assert call(variant="o128m128a", Nb=6) == B.MDNN_EINVAL and call(variant="o128m128b", No=6) == B.MDNN_EINVAL
 
 
 def test_variant_registry_and_choice(L):
@@ -122,6 +124,8 @@ def test_variant_registry_and_choice(L):
                   (7, 9, 9, 3, 5, 3, 1, 1)]:
         assert B.mdnn_choose_variant(*shape) in names
     assert B.mdnn_choose_variant(7, 9, 9, 3, 5, 3, 1, 1).endswith("s")     # scalar-load variant
+    assert B.mdnn_choose_variant(64, 56, 56, 256, 250, 3, 1, 1) == "o128m128a"    # only the filter count is odd
+    assert B.mdnn_choose_variant(50, 56, 56, 256, 256, 3, 1, 1) == "o128m128b"    # only the minibatch is
     assert B.mdnn_choose_variant(8, 2, 2, 1, 1, 3, 1, 0) is None          # invalid geometry
 
 

@@ -197,6 +197,9 @@ ODD = [
     ("k_odd",            8,  8,  8,  3, 32, 3, 1, 1, 1.0),     # K = 27: odd, one partial slab
     ("many_tiles",      32, 15, 13, 20, 200, 3, 1, 1, 1.0),    # several tiles both ways + tails
     ("long_k_chunked",   8,  6,  6, 520, 32, 3, 1, 1, 1.0),    # K = 4680 > one offset-table chunk
+    ("odd_filters",     32, 15, 13, 20, 202, 3, 1, 1, 1.0),    # only No off the multiple of 4: 4-byte filter copies alone
+    ("odd_batch",       30, 15, 13, 20, 200, 3, 1, 1, 0.5),    # only Nb: 4-byte patch copies and stores alone (M = 5850)
+    ("odd_batch_strided", 6, 17, 16, 7, 136, 5, 2, 2, 1.0),    # the same with an apron and a stride; M = 384
 ]
 
 
@@ -209,7 +212,10 @@ def test_odd_shapes_every_usable_variant(env, case):
     want, absum = oracle.conv_fprop(inp, filt, stride, pad, alpha)
     ran = 0
     for variant in [None] + B.mdnn_variant_names():
-        if variant is not None and not variant.endswith("s") and (Nb % 4 or No % 4):
+        try:          # a variant whose 16-byte copies this Nb or No rules out is refused
+            B.mdnn_describe_launch(Nb, Wi, Hi, Nc, No, Sk, stride, pad, variant)
+        except B.MdnnError:
+            assert variant is not None and (Nb % 4 or No % 4), variant
             continue
         say(f"[parity-odd] case={name} variant={variant} dims={L.dims()}")
         got = run_gpu(env, L, inp, filt, variant)

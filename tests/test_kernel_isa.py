@@ -75,10 +75,11 @@ def test_no_spills_and_register_budget(asm):
     assert spills and not any(spills) and not any(scratch)          # nothing ever goes to scratch memory
     names = re.findall(r"\.name:\s+(\S+)", asm)
     # Scalar registers parked in vector-register lanes: tolerated in the 4-byte-copy kernels
-    # (template argument VW = 1), which carry sixteen copy offsets per thread; elsewhere only a
+    # (template argument VW = 1, 14 or 41), which carry ten to sixteen copies per thread and slab,
+    # each with an LDS address of its own in a scalar register; elsewhere only a
     # few, and only outside every loop (the kernels that carry all piece bodies park a value or two
     # across a whole tile).
-    parked = {k: v for k, v in zip(names, sspills) if v and "Li1ELi2ELi32EEE" not in k}
+    parked = {k: v for k, v in zip(names, sspills) if v and not re.search(r"Li(1|14|41)ELi2ELi32EEE", k)}
     assert all(v <= 4 for v in parked.values()), parked
     for name in parked:
         body = asm[asm.index(name + ":"):asm.index(".size\t" + name)].splitlines()
