@@ -49,8 +49,10 @@ typedef enum mdnn_status {
  *
  * Arithmetic is fp32 throughout (fp32 matrix-core FMAs, no reduced-precision
  * conversion); the summation order is unspecified.  Any Nb >= 1 and No >= 1
- * give correct results; the fast kernels need Nb % 4 == 0 and No % 4 == 0,
- * other values take a slower scalar-load variant of the same kernel.
+ * give correct results; the fastest kernels need Nb % 4 == 0 and No % 4 == 0,
+ * other values take a variant of the same kernel that copies the operand
+ * concerned (filters for No, input patches for Nb) 4 bytes at a time, about a
+ * tenth slower.
  *
  * The caller owns all three buffers; out must not overlap in or filt.  The
  * call only enqueues work on `stream` (a hipStream_t; NULL = the default
@@ -72,11 +74,13 @@ mdnn_status mdnn_conv_fprop(const float* in, const float* filt, float* out,
  * built-in heuristic (for tests and tuning).  `variant` is one of the names
  * mdnn_variant_name() enumerates, or NULL / "" / "auto" for the heuristic.
  * A name may be followed by ':' and one letter that pins how tiles are cut into
- * the smaller blocks of Section 3.4: w = no tile is cut; h, t, q = the tiles of
- * the last partial round in halves, thirds (48 + 48 + 32 filter rows), quarters;
- * m = 128 of them in halves and the rest (at most 64) in quarters, all launched in
- * front of the whole tiles; H, T, Q = every tile so.  A cut the kernel does not
- * have, or that does not fit the tile count, is MDNN_EINVAL.
+ * the smaller blocks of Section 3.4: w = no tile is cut; h, t, q, e = the tiles
+ * of the last partial round in halves, thirds (48 + 48 + 32 filter rows),
+ * quarters, eighths (16 rows); m, n = 128 of them in halves and the rest in
+ * quarters (m, at most 64) or eighths (n, at most 32), p = 64 of them in quarters
+ * and the rest (at most 32) in eighths, all launched in front of the whole tiles;
+ * H, T, Q, E = every tile so.  A cut the kernel does not have, or that does not
+ * fit the tile count, is MDNN_EINVAL.
  * Every variant and cut computes the same function for every valid argument set.
  */
 mdnn_status mdnn_conv_fprop_variant(const float* in, const float* filt, float* out,

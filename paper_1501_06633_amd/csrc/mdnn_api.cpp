@@ -84,7 +84,7 @@ bool variant_usable(const mdnn::VariantInfo& v, int Nb, int No)
 // a partial round that keeps a few units busy for a whole tile time.  Cutting
 // them into pieces (less efficient, but short) can end the launch sooner.  The
 // cuts a kernel may offer: halves and quarters of a tile, and for 128-row tiles
-// "thirds" of 48 + 48 + 32 filter rows.
+// eighths of 16 filter rows and "thirds" of 48 + 48 + 32.
 // What was measured: workgroups that share a unit advance through the contraction
 // at the same rate (the matrix pipe alternates between their waves), so a piece
 // that starts beside a whole tile ends with it, whatever its height, and the two
@@ -111,8 +111,9 @@ struct Cut {
 
 // `force`: 0 = choose; 'w' = no cutting; 'h', 't', 'q', 'e' = the left-over tiles in halves, thirds,
 // quarters, eighths; 'H', 'T', 'Q', 'E' = every tile so; 'm', 'n' = 128 of the left-over tiles in halves
-// and the rest in quarters ('m') or eighths ('n'), all in front (tests and the block-size experiment
-// pin a cut this way).  A kernel that lacks the cut asked for returns n_whole = -1.
+// and the rest in quarters ('m') or eighths ('n'), 'p' = 64 of them in quarters and the rest in eighths,
+// all in front (tests and the block-size experiment pin a cut this way).  A kernel that lacks the
+// cut asked for, or a tile count outside the range of a pairing, returns n_whole = -1.
 Cut choose_cut(const mdnn::VariantInfo& v, int n_tiles, char force = 0)
 {
     Cut c = {n_tiles, 0, 0, 0, 0, 0.0, false};
