@@ -121,3 +121,51 @@ def test_pinned_cuts_on_random_shapes_bitwise():
             np.testing.assert_array_equal(y.cpu().numpy(), want, err_msg=f"{what} variant={v}")
             runs += 1
     assert runs == 30 * len(pinned) and paired >= 3
+
+
+def test_default_plans_with_one_to_five_rounds_of_tiles_bitwise():
+    """Sixty seeded shapes whose 128 x 128 tile count lies between one and five rounds of 256, with
+    the variant and the tail cut left to the library: halves, thirds, quarters, eighths, chains and
+    the pairings of two piece sizes all occur (asserted), filter tiles are ragged in a third of the
+    shapes, and the forward result and the data gradient (the same kernels on the turned-over
+    bank) must match the oracle bit for bit on integer data."""
+    import torch
+    from paper_1501_06633_amd import binding as B
+    import oracle
+
+    rng = np.random.default_rng(2718)
+    seen = set()
+    for it in range(60):
+        Nb = int(rng.choice([32, 64, 128]))
+        No = int(rng.choice([128, 128, 200, 256, 256, 384]))
+        want_tiles = int(rng.integers(257, 1300))
+        col_tiles = max(1, want_tiles // -(-No // 128))
+        pixels = max(1, col_tiles * 128 // Nb)
+        Ho = int(rng.integers(1, 24))
+        Wo = max(1, pixels // Ho)
+        Sk = int(rng.choice([1, 3]))
+        pad = int(rng.integers(0, Sk))
+        Hi, Wi = Ho + Sk - 1 - 2 * pad, Wo + Sk - 1 - 2 * pad
+        if Hi < 1 or Wi < 1:
+            Hi, Wi, pad = Ho + Sk - 1, Wo + Sk - 1, 0
+        Nc = int(rng.integers(1, 5))
+        alpha = float(rng.choice([1.0, 0.5]))
+        plan = B.mdnn_describe_launch(Nb, Wi, Hi, Nc, No, Sk, 1, pad)
+        cut = tuple(k for k in ("halved", "thirded", "quartered", "eighthed") if plan[k])
+        seen.add((plan["variant"], cut, plan["pieces_first"] > 0, plan["pieces"] > plan["pieces_first"]))
+        x = rng.integers(-4, 5, size=(Nc, Hi, Wi, Nb)).astype(np.float32)
+        w = rng.integers(-4, 5, size=(Nc, Sk, Sk, No)).astype(np.float32)
+        g = rng.integers(-4, 5, size=(No, plan["M"] // Nb // (Wi + 2 * pad - Sk + 1), Wi + 2 * pad - Sk + 1, Nb)).astype(np.float32)
+        what = f"case={it} Nb={Nb} Hi={Hi} Wi={Wi} Nc={Nc} No={No} Sk={Sk} pad={pad} alpha={alpha} plan={plan}"
+        print(what, flush=True)
+        d_x, d_w, d_g = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), torch.from_numpy(g).cuda()
+        y = B.mdnn_conv_fprop(d_x, d_w, 1, pad, alpha)
+        dx = B.mdnn_conv_bprop_data(d_g, d_w, (Hi, Wi), 1, pad, alpha)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(y.cpu().numpy(), oracle.conv_fprop(x, w, 1, pad, alpha, want_abs=False), err_msg=what)
+        np.testing.assert_array_equal(dx.cpu().numpy(), oracle.conv_bprop_data(g, w, (Hi, Wi), 1, pad, alpha, want_abs=False),
+                                      err_msg=what)
+    cuts = {c for _, c, _, _ in seen}
+    for need in [("halved",), ("quartered",), ("eighthed",), ("thirded",), ("halved", "eighthed"), ("halved", "quartered")]:
+        assert need in cuts, (need, sorted(cuts))
+    assert any(first and behind for _, _, first, behind in seen)      # pieces in front of and behind the whole tiles
