@@ -199,3 +199,38 @@ def test_result_beyond_two_gib(env):
     vals, _ = oracle.conv_bprop_data_points(dout, filt, idx, (Hi, Wi), stride, pad, alpha)
     np.testing.assert_array_equal(sampled, vals)
     assert np.abs(vals).max() > 0
+
+
+# Stride-2 3x3 layers with 32 input channels: the residue-class problem has 4 * 32 = 128 filters of
+# 2 x 2 taps and one 128-column tile per pixel of the (Ho + 1) x (Wo + 1) class grid at minibatch
+# 128, so the tile count -- and with it the tail cut of the scattering kernel -- is (Ho + 1)(Wo + 1).
+SCATTER_TAILS = [
+    # Ho  Wo  what the plan of the class problem must contain
+    (13, 19, dict(tiles=280, eighthed=24)),                     # eighths beside one round
+    (12, 25, dict(tiles=338, thirded=82)),                      # thirds
+    (14, 22, dict(tiles=345, quartered=64, eighthed=25)),       # a quarter and an eighth per unit
+    (13, 27, dict(tiles=392, halved=128, eighthed=8)),          # a half and an eighth per unit
+    (19, 26, dict(tiles=540, whole=512, eighthed=28)),          # eighths in front of two rounds
+]
+
+
+@pytest.mark.parametrize("Ho,Wo,want", SCATTER_TAILS, ids=[f"{c[2]['tiles']}_tiles" for c in SCATTER_TAILS])
+def test_scattering_epilogue_in_every_tail_piece_bitwise(env, Ho, Wo, want):
+    """The strided data gradient scatters straight from the accumulators into din; when the class
+    problem's last round of tiles is cut, the half, third, quarter and eighth bodies do the
+    scattering.  Integer data, whole tensor, bit for bit."""
+    torch, B, oracle = env
+    Nb, Nc, No, Sk, stride, pad, alpha = 128, 32, 4, 3, 2, 0, 0.5
+    Hi, Wi = 2 * Ho + 1, 2 * Wo + 1
+    assert oracle.out_dims(Wi, Hi, Sk, stride, pad) == (Wo, Ho)
+    plan = B.mdnn_describe_launch(Nb, Wo, Ho, No, stride * stride * Nc, 2, 1, 1)    # the class problem, as the library plans it
+    say(f"[bprop-scatter-tails] Ho={Ho} Wo={Wo} plan={plan}")
+    for k, v in want.items():
+        assert plan[k] == v, (k, plan)
+    rng = np.random.default_rng(500 + Ho * Wo)
+    dout = rng.integers(-4, 5, size=(No, Ho, Wo, Nb)).astype(np.float32)
+    filt = rng.integers(-4, 5, size=(Nc, Sk, Sk, No)).astype(np.float32)
+    got = B.mdnn_conv_bprop_data(torch.from_numpy(dout).cuda(), torch.from_numpy(filt).cuda(), (Hi, Wi), stride, pad, alpha)
+    torch.cuda.synchronize()
+    wanted = oracle.conv_bprop_data(dout, filt, (Hi, Wi), stride, pad, alpha, want_abs=False)
+    np.testing.assert_array_equal(got.cpu().numpy(), wanted)
