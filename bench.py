@@ -190,6 +190,9 @@ def main():
                     help="skip the check of the timed output buffers against the oracle (stratified points)")
     ap.add_argument("--vgg16", action="store_true",
                     help="time the nine distinct 3x3 shapes of a VGG-16 style network at minibatch 64")
+    ap.add_argument("--tail-cuts", action="store_true",
+                    help="time layers with 280 ... 1568 tiles of 128x128 under every way of cutting the last "
+                         "partial round of tiles (pinned through the variant name) beside the library's own choice")
     ap.add_argument("--minibatch", action="store_true",
                     help="time the headline layer's geometry at minibatch sizes 4 ... 256")
     ap.add_argument("--block-sizes", action="store_true",
@@ -564,6 +567,54 @@ def main():
                     del d_in, d_f, out
         result["variant_sweep"] = {"shapes": rows, "worst_auto_slower_by": round(worst, 4)}
         log(f"[bench] sweep: the library's choice is at most {100 * worst:.1f}% slower than the best variant")
+
+    if args.tail_cuts:
+        # Section 3.4's smaller blocks, used for the last partial round of tiles only: 3x3 layers
+        # with 256 input channels whose count of 128x128 tiles leaves r = 24 ... 150 tiles beyond
+        # whole rounds of 256, each timed with the library's plan and with every pinned cut the two
+        # 128x128 kernels offer for that r (w: none, h/t/q/e: halves, thirds, quarters, eighths,
+        # m/n/p: pairings of two piece sizes per compute unit).
+        def timed(fn, n):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+        shapes = [  # name, Nb, Hi, Wi, Nc, No
+            ("280 tiles (r = 24)", 128, 10, 14, 256, 256), ("338 tiles (r = 82; AlexNet-v2 conv5)", 128, 13, 13, 256, 256),
+            ("352 tiles (r = 96)", 128, 11, 16, 256, 256), ("392 tiles (r = 136; VGG conv5_1)", 64, 14, 14, 512, 512),
+            ("406 tiles (r = 150)", 128, 7, 29, 256, 256), ("540 tiles (2 rounds + 28)", 128, 12, 15, 256, 384),
+            ("800 tiles (3 rounds + 32; Overfeat L2 geometry)", 128, 20, 20, 256, 256),
+            ("1568 tiles (6 rounds + 32; VGG conv4_1)", 64, 28, 28, 256, 512)]
+        rows = {}
+        for name, nb, hi, wi, nc, no in shapes:
+            d_in = torch.rand((nc, hi, wi, nb), device="cuda") - 0.5
+            d_f = torch.randn((nc, 3, 3, no), device="cuda") * 0.01
+            out = torch.empty((no, hi, wi, nb), device="cuda")
+            fl = B.mdnn_conv_flops(nb, wi, hi, nc, no, 3)
+            res = {}
+            for v in [None] + [f"{k}:{c}" for k in ("o128m128", "o128m128k8") for c in "whtqemnp"]:
+                try:
+                    plan = B.mdnn_describe_launch(nb, wi, hi, nc, no, 3, 1, 1, v)
+                except B.MdnnError:
+                    continue                      # this kernel has no such cut for this tile count
+                fn = lambda: B.mdnn_conv_fprop(d_in, d_f, 1, 1, 1.0, out=out, variant=v)
+                w = timed(fn, 3)
+                timed(fn, int(40.0 / max(w, 1e-3)) + 1)
+                ms = min(timed(fn, 20), timed(fn, 20), timed(fn, 20))
+                cut = "/".join(f"{plan[k]}{k[0]}" for k in ("halved", "thirded", "quartered", "eighthed") if plan[k]) or "uncut"
+                res[v or "library"] = {"ms": round(ms, 4), "frac_peak": round(fl / ms / 1e9 / PEAK_FP32_MATRIX_TFLOPS, 4),
+                                       "variant": plan["variant"], "cut": cut, "pieces_first": plan["pieces_first"]}
+            rows[name] = res
+            best = min(res, key=lambda k: res[k]["ms"])
+            log(f"[bench] tail cuts, {name}: library = {res['library']['variant']} {res['library']['cut']} "
+                f"{100 * res['library']['frac_peak']:.1f}%; best = {best} {100 * res[best]['frac_peak']:.1f}%")
+            for k, r in res.items():
+                log(f"[bench]     {k:14s} {r['ms'] * 1e3:8.1f} us {100 * r['frac_peak']:5.1f}%  {r['cut']}")
+            del d_in, d_f, out
+        result["tail_cuts"] = rows
 
     if args.vgg16:
         # the nine distinct 3x3 shapes of a VGG-16 style network at minibatch 64; random data made on
