@@ -155,15 +155,21 @@ Cut choose_cut(const mdnn::VariantInfo& v, int n_tiles, char force = 0)
     // three-per-unit kernel).
     if (v.thirds && 3 * r <= kComputeUnits && n_tiles < 2 * kComputeUnits) take(0.375 / e3, 0, r, 0);
     if (v.max_split >= 4) take(rounds_of(4) / e4, 0, 0, r);
-    // Eighths where they leave one 16-row piece per unit at most -- and only where every workgroup
-    // of the launch is resident from the start, so that nothing depends on where the dispatcher
-    // puts what comes later.  On the three-per-unit kernel that is beside exactly two rounds (540
-    // tiles: 90.7 % of peak against 86.3 % with quarters; beside one round the quarter is as fast;
-    // beside three or six rounds 71 % against 89.5 %: the whole tiles that do not fit at first land
-    // three to a unit).  On the two-per-unit kernel beside one round (280 tiles: 81.4 against
-    // 78.3 %; beside two: 81.9 against 84.9 %).
-    if (v.max_split >= 8 && 8 * r <= kComputeUnits && n_tiles / kComputeUnits == (v.est_wg_per_cu >= 3 ? 2 : 1))
-        take(0.125 / e8, 0, 0, 0, r);
+    // Eighths where they leave one 16-row piece per unit at most.  They go in front of the whole
+    // tiles, one per unit, and so take a slot of the first wave of workgroups from a whole tile each.
+    // On the three-per-unit kernel that is harmless when the whole tiles do not fill their last wave
+    // of 768 anyway (R = 2, 4, 5, 7, 8 rounds of 256: +1 ... +4 % over quarters; 540 tiles: 90.7 %
+    // of peak against 86.3 %) and costs a quarter of the launch when they do (R = 3, 6: 800 tiles
+    // 70 % against 87 %, 1568 tiles 80 against 90 %: the displaced whole tiles form a wave of their
+    // own and land three to a unit); beside a single round the quarter is as fast.  On the
+    // two-per-unit kernel only beside one round, where every workgroup is resident from the start
+    // (280 tiles: 81.4 against 78.3 %); beside more the outcome differs from shape to shape
+    // (540 tiles in three filter tiles: 80.1 against 84.3 %; 528 tiles in one: 84.2 against 80.4 %).
+    {
+        const int R = n_tiles / kComputeUnits;
+        const bool fits = v.est_wg_per_cu >= 3 ? (R >= 2 && R % 3 != 0) : R == 1;
+        if (v.max_split >= 8 && 8 * r <= kComputeUnits && fits) take(0.125 / e8, 0, 0, 0, r);
+    }
     // One round of whole tiles on a kernel that holds three workgroups per unit: a whole tile and
     // two pieces per unit, all started together (pieces in front), end together; chains of equal
     // pieces run their tail alone.

@@ -140,10 +140,10 @@ def test_choice_between_the_two_128x128_tiles_follows_the_tile_count(L):
         assert plan(Hi)["tiles"] <= 512 and pick(Hi) == "o128m128", Hi
     for Hi in (18, 23, 24, 26, 28):                             # 576 ... 896 tiles: at most 768 whole ones
         assert plan(Hi)["whole"] <= 768 and pick(Hi) == "o128m128k8", Hi
-    for Hi in (31, 32, 33, 35):                                 # 992, 1024, 1056, 1120 tiles
+    for Hi in (31, 32, 35):                                     # 992, 1024, 1120 tiles
         d = plan(Hi)
         assert 768 < d["whole"] < 1248 and d["pieces"] < 256 and pick(Hi) == "o128m128", Hi
-    for Hi in (34, 36):                                         # 1088, 1152 tiles: 1024 whole + 256 pieces in front
+    for Hi in (33, 34, 36):                                     # 1056 (eighths), 1088, 1152 tiles: 1024 whole + 256 pieces in front
         d = plan(Hi)
         assert d["whole"] == 1024 and d["pieces_first"] == 256 and pick(Hi) == "o128m128k8", Hi
     for Hi in (39, 40, 48, 80):                                 # 1248 tiles and more
@@ -221,15 +221,17 @@ def test_how_the_last_round_is_cut(L):
     assert cut(65, "o128m128") == (3, 0, 65, 0) and cut(82, "o128m128") == (3, 0, 82, 0)
     assert cut(85, "o128m128") == (3, 0, 85, 0) and cut(86, "o128m128") == (2, 86, 0, 0)
     assert cut(82, "o128m128k8") == (2, 82, 0, 0)
-    # eighths: beside one round on the two-per-unit kernel, beside exactly two on the three-per-unit one
+    # eighths: beside one round on the two-per-unit kernel; on the three-per-unit one beside two or more
+    # rounds unless the whole tiles fill their last wave of 768
     assert cut(24, "o128m128") == (8, 0, 0, 0, 24) and cut(32, "o128m128") == (8, 0, 0, 0, 32) and cut(33, "o128m128") == (4, 0, 0, 33)
     assert cut(24, "o128m128k8") == (4, 0, 0, 24)
     d = B.mdnn_describe_launch(128, 2 + 1, 2 + 540, 4, 128, 3, 1, 0, "o128m128k8")
     assert (d["whole"], d["split"], d["eighthed"], d["pieces"], d["pieces_first"]) == (512, 8, 28, 224, 224)
     d = B.mdnn_describe_launch(128, 2 + 1, 2 + 540, 4, 128, 3, 1, 0, "o128m128")
     assert (d["whole"], d["split"], d["quartered"]) == (512, 4, 28)
-    d = B.mdnn_describe_launch(128, 2 + 1, 2 + 800, 4, 128, 3, 1, 0, "o128m128k8")
-    assert (d["whole"], d["split"], d["quartered"]) == (768, 4, 32)
+    for tiles, eighths in ((800, False), (1056, True), (1300, True), (1560, False), (1810, True)):   # 3, 4, 5, 6, 7 rounds
+        d = B.mdnn_describe_launch(128, 2 + 1, 2 + tiles, 4, 128, 3, 1, 0, "o128m128k8")
+        assert (d["split"], d["eighthed"] > 0, d["quartered"] > 0) == ((8, True, False) if eighths else (4, False, True)), tiles
     # thirds only beside at most one round of whole tiles: 512 + 76 tiles are halved
     d = B.mdnn_describe_launch(128, 2 + 1, 2 + 588, 4, 128, 3, 1, 0, "o128m128")
     assert (d["tiles"], d["whole"], d["split"], d["halved"]) == (588, 512, 2, 76)
