@@ -146,47 +146,48 @@ Cut choose_cut(const mdnn::VariantInfo& v, int n_tiles, char force = 0)
     auto take = [&](double cost, int nh, int nt, int nq, int ne = 0, bool pair = false) {
         if (cost < c.cost - 0.05) { c.cost = cost;  c.n_half = nh;  c.n_third = nt;  c.n_quarter = nq;  c.n_eighth = ne;  c.pair_up = pair; }
     };
-    const bool one_round = n_tiles > kComputeUnits && n_tiles < 2 * kComputeUnits;
+    const int R = n_tiles / kComputeUnits;
+    if (v.max_split >= 8 && R >= 1) {
+        // The two 128 x 128 kernels, which have every piece size.  Measured over R = 1 ... 8 rounds
+        // and r = 8 ... 248 left-over tiles on four layer families (3x3 with 128, 256 and 384
+        // filters, 5x5 with 256), every cut pinned in turn.  With pieces of one size the best cut
+        // follows the rows on the busiest unit at every R:
+        //     r <= 32 eighths (16 rows) | <= 64 quarters (32) | <= 128 halves (64) | <= 192 quarters in
+        //     chains of up to three | beyond: whole tiles,
+        // with thirds (48 rows) for 64 < r <= 85 on the two-per-unit kernel when the whole tiles leave
+        // half of their last wave of 512 free (R odd: +1.5 ... +6 points over halves; R even: 62 ... 80 %
+        // against 81 ... 88 %).  Pairings of two sizes per
+        // unit (<= 96: a quarter and an eighth; <= 160: a half and an eighth; <= 192: a half and a
+        // quarter; all pieces in front) need room for up to 512 pieces beside the whole tiles:
+        //   - three-per-unit kernel: the last wave of 768 must hold only 256 whole tiles (R mod 3 = 1;
+        //     +1 ... +6 points over chains and halves on all four families); with 512 in it (R = 2, 5)
+        //     the half pairings fall to 65 ... 82 %, the quarter-and-eighth pairing still holds;
+        //   - two-per-unit kernel: steady on the 3x3 families, but 79.8 % against 89.5 % and 84.5 %
+        //     against 89.5 % on two 5x5 layers five rounds long -- not taken.
+        // Whole tiles that fill their last wave exactly (three-per-unit kernel, R mod 3 = 0) leave
+        // no room for any piece in front: halves swing between 75 and 91 % from shape to shape,
+        // eighths between 67 and 82 %; quarters, alone or in chains, are the steady choice (83 ... 91 %).
+        // (Beyond eight rounds, where nothing was measured and the tail is a few per cent of the
+        // launch, a full last wave only rules out the eighths.)
+        const bool three = v.est_wg_per_cu >= 3;
+        const bool full_wave = three && R % 3 == 0;
+        if (full_wave && R <= 8) {
+            if (r <= 192) take(rounds_of(4) / e4, 0, 0, r);
+        } else if (r <= 32 && !(three && R == 1) && !full_wave) take(0.125 / e8, 0, 0, 0, r);
+        else if (r <= 64)                          take(0.25 / e4, 0, 0, r);
+        else if (r <= 85 && v.thirds && R % 2 == 1) take(0.375 / e3, 0, r, 0);
+        else if (r <= 96 && three && !full_wave)   take(0.40, 0, 0, 64, r - 64, true);
+        else if (r <= 128)                         take(0.5 / e2, r, 0, 0);
+        else if (r <= 160 && three && R % 3 == 1)  take(0.65, 128, 0, 0, r - 128, true);
+        else if (r <= 192 && three && R % 3 == 1)  take(0.78, 128, 0, r - 128, 0, true);
+        else if (r <= 192)                         take(rounds_of(4) / e4, 0, 0, r);
+        if (c.pieces() > 0) c.n_whole = n_tiles - r;
+        return c;
+    }
     take(rounds_of(2) / e2, r, 0, 0);
-    // Thirds only beside at most one round of whole tiles.  With two rounds on a kernel that holds
-    // two workgroups per unit, piece and first whole tile end together, both slots of every unit
-    // free at once, and the dispatcher then places the second round two to a unit on half the
-    // units (588 tiles of 128 x 128: 64.6 % of peak against 84.5 % with halves on the
-    // three-per-unit kernel).
+    // Thirds only beside at most one round of whole tiles (kernels without eighths have none today).
     if (v.thirds && 3 * r <= kComputeUnits && n_tiles < 2 * kComputeUnits) take(0.375 / e3, 0, r, 0);
     if (v.max_split >= 4) take(rounds_of(4) / e4, 0, 0, r);
-    // Eighths where they leave one 16-row piece per unit at most.  They go in front of the whole
-    // tiles, one per unit, and so take a slot of the first wave of workgroups from a whole tile each.
-    // On the three-per-unit kernel that is harmless when the whole tiles do not fill their last wave
-    // of 768 anyway (R = 2, 4, 5, 7, 8 rounds of 256: +1 ... +4 % over quarters; 540 tiles: 90.7 %
-    // of peak against 86.3 %) and costs a quarter of the launch when they do (R = 3, 6: 800 tiles
-    // 70 % against 87 %, 1568 tiles 80 against 90 %: the displaced whole tiles form a wave of their
-    // own and land three to a unit); beside a single round the quarter is as fast.  On the
-    // two-per-unit kernel only beside one round, where every workgroup is resident from the start
-    // (280 tiles: 81.4 against 78.3 %); beside more the outcome differs from shape to shape
-    // (540 tiles in three filter tiles: 80.1 against 84.3 %; 528 tiles in one: 84.2 against 80.4 %).
-    {
-        const int R = n_tiles / kComputeUnits;
-        const bool fits = v.est_wg_per_cu >= 3 ? (R >= 2 && R % 3 != 0) : R == 1;
-        if (v.max_split >= 8 && 8 * r <= kComputeUnits && fits) take(0.125 / e8, 0, 0, 0, r);
-    }
-    // One round of whole tiles on a kernel that holds three workgroups per unit: a whole tile and
-    // two pieces per unit, all started together (pieces in front), end together; chains of equal
-    // pieces run their tail alone.
-    //   128 < r <= 192: a half and a quarter, (128 + 64 + 32) / 128 tile times (386 ... 446 tiles:
-    //       125 us against 129 us for the best other choice);
-    //   128 < r <= 160: a half and an eighth, (128 + 64 + 16) / 128 (392 tiles of a 14 x 14 layer
-    //       with 512 channels: 85.8 % of peak against 80.0 %; 406 tiles: 86.8 against 81.1 %);
-    //   85 < r <= 96: a quarter and an eighth, (128 + 32 + 16) / 128 (352 tiles: 87.4 % against
-    //       83.4 % with halves; up to 85 the 48-row thirds of the deep-slab kernel do as well).
-    // Only with one round: with two or three, everything that starts together ends together and
-    // the dispatcher then packs the next round three to a unit on a third of the units (255 us
-    // against 194 us), with four or five the gain is under 1 %.
-    if (v.max_split >= 4 && v.est_wg_per_cu >= 3 && one_round) {
-        if (v.max_split >= 8 && r > 128 && r <= 160) take(0.65, 128, 0, 0, r - 128, true);
-        else if (r > 128 && r <= 192)                take(0.75, 128, 0, r - 128, 0, true);
-        if (v.max_split >= 8 && r > 85 && r <= 96)   take(0.40, 0, 0, 64, r - 64, true);
-    }
     if (c.pieces() > 0) c.n_whole = n_tiles - r;
     return c;
 }
@@ -220,6 +221,11 @@ double variant_cost(const mdnn::VariantInfo& v, int No, int64_t M)
                                          n_pieces < kComputeUnits;
         eff = tiles <= 2 * kComputeUnits ? v.eff_few : v.eff;
         if (partial_second_wave) eff = 0.82 * v.eff_few;
+        // Whole tiles that fill their last wave of 768 exactly leave no room for the tail pieces
+        // (see choose_cut()): up to six rounds the two-per-unit kernel is the steadier choice
+        // (three or six rounds + 24 ... 48 tiles: 86 ... 88.5 % against 89.5 ... 91 %).
+        const int64_t R = tiles / kComputeUnits;
+        if (v.est_wg_per_cu == 3 && n_pieces > 0 && R % 3 == 0 && R <= 6) eff *= 0.985;
     } else {
         eff = 8 * tiles < 39 * kComputeUnits ? v.eff_few : v.eff;
     }

@@ -130,22 +130,25 @@ def test_variant_registry_and_choice(L):
 
 
 def test_choice_between_the_two_128x128_tiles_follows_the_tile_count(L):
-    """128 images per pixel, 256 filters: 2 * Hi * 16 tiles of 128x128.  The three-per-CU tile takes
-    every launch of more than two rounds except those whose whole tiles fill the 768 slots once and
-    partly a second time with fewer than 256 pieces in front (measured at 73-82 %); the two-per-CU
-    tile takes those and everything up to two rounds."""
+    """128 images per pixel, 256 filters: 2 * Hi * 16 tiles of 128x128.  The two-per-CU tile takes
+    everything up to two rounds; the three-per-CU tile takes longer launches except (a) those whose
+    whole tiles fill the 768 slots once and partly a second time with fewer than 256 pieces in
+    front (measured at 73-82 %) and (b) launches of up to six rounds whose whole tiles fill their
+    last wave of 768 exactly and that have tail pieces to place (the pieces then have no room)."""
     pick = lambda Hi: B.mdnn_choose_variant(128, 16, Hi, 256, 256, 3, 1, 1)
     plan = lambda Hi: B.mdnn_describe_launch(128, 16, Hi, 256, 256, 3, 1, 1, "o128m128k8")
     for Hi in (8, 12, 16):                                      # up to two rounds
         assert plan(Hi)["tiles"] <= 512 and pick(Hi) == "o128m128", Hi
-    for Hi in (18, 23, 24, 26, 28):                             # 576 ... 896 tiles: at most 768 whole ones
+    for Hi in (18, 20, 23, 24):                                 # 576 ... 768 tiles: two rounds and a tail, or 768 whole
         assert plan(Hi)["whole"] <= 768 and pick(Hi) == "o128m128k8", Hi
-    for Hi in (31, 32, 35):                                     # 992, 1024, 1120 tiles
+    for Hi in (26, 28):                                         # 832, 896 tiles: 768 whole ones and a tail
+        assert plan(Hi)["whole"] == 768 and plan(Hi)["pieces"] > 0 and pick(Hi) == "o128m128", Hi
+    for Hi in (31, 32):                                         # 992, 1024 tiles
         d = plan(Hi)
         assert 768 < d["whole"] < 1248 and d["pieces"] < 256 and pick(Hi) == "o128m128", Hi
-    for Hi in (33, 34, 36):                                     # 1056 (eighths), 1088, 1152 tiles: 1024 whole + 256 pieces in front
+    for Hi in (33, 34, 35, 36):                                 # 1056 ... 1152 tiles: 1024 whole + 256 or more pieces in front
         d = plan(Hi)
-        assert d["whole"] == 1024 and d["pieces_first"] == 256 and pick(Hi) == "o128m128k8", Hi
+        assert d["whole"] == 1024 and d["pieces_first"] >= 256 and pick(Hi) == "o128m128k8", Hi
     for Hi in (39, 40, 48, 80):                                 # 1248 tiles and more
         assert pick(Hi) == "o128m128k8", Hi
 
@@ -199,52 +202,44 @@ def test_describe_launch(L):
 
 
 def test_how_the_last_round_is_cut(L):
-    """128 images, 128 filters, 3x3 unpadded: Ho * Wo tiles of 128x128.  What becomes of the
-    r = tiles mod 256 left-over tiles: eighths up to 32 (where measured to pay), quarters up to 64,
-    thirds (48 + 48 + 32 rows; the deep-slab kernel only) up to 85, halves up to 128, quarters (up
-    to three per unit) up to 192, then whole tiles; beside a single round the three-per-unit
-    kernel gives every unit a whole tile and two pieces of different heights."""
-    def cut(r, variant):
-        d = B.mdnn_describe_launch(128, 2 + 16, 2 + (16 + r // 16), 4, 128, 3, 1, 0, variant) if r % 16 == 0 else \
-            B.mdnn_describe_launch(128, 2 + 1, 2 + (256 + r), 4, 128, 3, 1, 0, variant)
-        assert d["tiles"] == 256 + r and d["whole"] + d["halved"] + d["thirded"] + d["quartered"] + d["eighthed"] == d["tiles"]
-        if d["eighthed"]:
-            return d["split"], d["halved"], d["thirded"], d["quartered"], d["eighthed"]
-        return d["split"], d["halved"], d["thirded"], d["quartered"]
-    for v in ("o128m128", "o128m128k8"):
-        assert cut(0, v) == (1, 0, 0, 0)
-        assert cut(40, v) == (4, 0, 0, 40) and cut(64, v) == (4, 0, 0, 64)
-        assert cut(100, v) == (2, 100, 0, 0) and cut(128, v) == (2, 128, 0, 0)
-        if v == "o128m128":
-            assert cut(129, v) == (4, 0, 0, 129) and cut(176, v) == (4, 0, 0, 176) and cut(192, v) == (4, 0, 0, 192)
-        assert cut(200, v) == (1, 0, 0, 0) and cut(255, v) == (1, 0, 0, 0)
-    assert cut(65, "o128m128") == (3, 0, 65, 0) and cut(82, "o128m128") == (3, 0, 82, 0)
-    assert cut(85, "o128m128") == (3, 0, 85, 0) and cut(86, "o128m128") == (2, 86, 0, 0)
-    assert cut(82, "o128m128k8") == (2, 82, 0, 0)
-    # eighths: beside one round on the two-per-unit kernel; on the three-per-unit one beside two or more
-    # rounds unless the whole tiles fill their last wave of 768
-    assert cut(24, "o128m128") == (8, 0, 0, 0, 24) and cut(32, "o128m128") == (8, 0, 0, 0, 32) and cut(33, "o128m128") == (4, 0, 0, 33)
-    assert cut(24, "o128m128k8") == (4, 0, 0, 24)
+    """128 images, 128 filters, 3x3 unpadded: Ho * Wo tiles of 128x128, R whole rounds of 256 and
+    r left-over tiles.  Pieces of one size: eighths up to r = 32, quarters up to 64, halves up to
+    128, quarters in chains up to 192, then whole tiles; thirds (the deep-slab kernel) for 65 ... 85
+    when R is odd.  Pairings of two sizes per unit (three-per-unit kernel): a quarter and an eighth
+    for 65 ... 96 unless R mod 3 = 0, a half and an eighth (to 160) or a quarter (to 192) when
+    R mod 3 = 1.  R mod 3 = 0 up to eight rounds on that kernel: quarters only."""
+    def cut(r, variant, R=1):
+        d = B.mdnn_describe_launch(128, 2 + 1, 2 + (256 * R + r), 4, 128, 3, 1, 0, variant)
+        assert d["tiles"] == 256 * R + r and d["whole"] + d["halved"] + d["thirded"] + d["quartered"] + d["eighthed"] == d["tiles"]
+        assert d["whole"] == (d["tiles"] if d["pieces"] == 0 else 256 * R)
+        return "".join(f"{d[k]}{k[0]}" for k in ("halved", "thirded", "quartered", "eighthed") if d[k]) or "w"
+    for R in (1, 2, 3, 4, 5, 7, 10):
+        for v in ("o128m128", "o128m128k8"):
+            three, full = v == "o128m128k8", v == "o128m128k8" and R % 3 == 0
+            assert cut(0, v, R) == "w" and cut(200, v, R) == "w" and cut(255, v, R) == "w"
+            assert cut(40, v, R) == "40q" and cut(64, v, R) == "64q"
+            assert cut(24, v, R) == ("24q" if full or (three and R == 1) else "24e"), (v, R)
+            assert cut(32, v, R) == ("32q" if full or (three and R == 1) else "32e") and cut(33, v, R) == "33q"
+            if three:
+                assert cut(72, v, R) == ("72q" if full and R <= 8 else "72h" if full else "64q8e"), (v, R)
+                assert cut(96, v, R) == ("96q" if full and R <= 8 else "96h" if full else "64q32e")
+                assert cut(136, v, R) == ("128h8e" if R % 3 == 1 else "136q"), (v, R)
+                assert cut(160, v, R) == ("128h32e" if R % 3 == 1 else "160q")
+                assert cut(161, v, R) == ("128h33q" if R % 3 == 1 else "161q") and cut(192, v, R) == ("128h64q" if R % 3 == 1 else "192q")
+                assert cut(100, v, R) == ("100q" if full and R <= 8 else "100h") and cut(128, v, R) == ("128q" if full and R <= 8 else "128h")
+            else:
+                assert cut(65, v, R) == ("65t" if R % 2 else "65h") and cut(85, v, R) == ("85t" if R % 2 else "85h")
+                assert cut(86, v, R) == "86h" and cut(128, v, R) == "128h"
+                assert cut(129, v, R) == "129q" and cut(192, v, R) == "192q"
+    # where the pieces go: pairings all in front, single sizes up to one per unit in front of two or more rounds
+    d = B.mdnn_describe_launch(128, 2 + 1, 2 + 392, 4, 128, 3, 1, 0, "o128m128k8")
+    assert (d["whole"], d["pieces"], d["pieces_first"]) == (256, 320, 320)
     d = B.mdnn_describe_launch(128, 2 + 1, 2 + 540, 4, 128, 3, 1, 0, "o128m128k8")
     assert (d["whole"], d["split"], d["eighthed"], d["pieces"], d["pieces_first"]) == (512, 8, 28, 224, 224)
-    d = B.mdnn_describe_launch(128, 2 + 1, 2 + 540, 4, 128, 3, 1, 0, "o128m128")
-    assert (d["whole"], d["split"], d["quartered"]) == (512, 4, 28)
-    for tiles, eighths in ((800, False), (1056, True), (1300, True), (1560, False), (1810, True)):   # 3, 4, 5, 6, 7 rounds
-        d = B.mdnn_describe_launch(128, 2 + 1, 2 + tiles, 4, 128, 3, 1, 0, "o128m128k8")
-        assert (d["split"], d["eighthed"] > 0, d["quartered"] > 0) == ((8, True, False) if eighths else (4, False, True)), tiles
-    # thirds only beside at most one round of whole tiles: 512 + 76 tiles are halved
-    d = B.mdnn_describe_launch(128, 2 + 1, 2 + 588, 4, 128, 3, 1, 0, "o128m128")
-    assert (d["tiles"], d["whole"], d["split"], d["halved"]) == (588, 512, 2, 76)
-    # beside a single round, the three-per-unit kernel gives every unit two pieces: a half with an
-    # eighth (to 160) or a quarter (to 192), a quarter with an eighth (86 ... 96)
-    assert cut(136, "o128m128") == (4, 0, 0, 136) and cut(136, "o128m128k8") == (0, 128, 0, 0, 8)
-    assert cut(160, "o128m128k8") == (0, 128, 0, 0, 32) and cut(161, "o128m128k8") == (0, 128, 0, 33)
-    assert cut(192, "o128m128k8") == (0, 128, 0, 64) and cut(129, "o128m128k8") == (0, 128, 0, 0, 1)
-    assert cut(86, "o128m128k8") == (0, 0, 0, 64, 22) and cut(96, "o128m128k8") == (0, 0, 0, 64, 32) and cut(97, "o128m128k8") == (2, 97, 0, 0)
-    d = B.mdnn_describe_launch(128, 2 + 1, 2 + 392, 4, 128, 3, 1, 0, "o128m128k8")
-    assert (d["whole"], d["pieces"], d["pieces_first"]) == (256, 320, 320)          # all pieces in front
-    d = B.mdnn_describe_launch(128, 2 + 1, 2 + 648, 4, 128, 3, 1, 0, "o128m128k8")   # two rounds + 136: quarters
-    assert (d["whole"], d["split"], d["quartered"]) == (512, 4, 136)
+    d = B.mdnn_describe_launch(128, 2 + 1, 2 + 648, 4, 128, 3, 1, 0, "o128m128k8")   # two rounds + 136: quarter chains
+    assert (d["whole"], d["split"], d["quartered"], d["pieces_first"]) == (512, 4, 136, 256)
+    d = B.mdnn_describe_launch(128, 2 + 1, 2 + 280, 4, 128, 3, 1, 0, "o128m128")     # one round: the pieces go behind
+    assert (d["whole"], d["split"], d["eighthed"], d["pieces_first"]) == (256, 8, 24, 0)
     d = B.mdnn_describe_launch(128, 2 + 1, 2 + 136, 4, 128, 3, 1, 0, "o128m128k8")   # no whole round at all
     assert d["whole"] == 0 and d["split"] in (2, 4)
     assert L.mdnn_describe_launch(8, 9, 9, 1, 4, 3, 1, 0, None, None, 0) == B.MDNN_ENULL
