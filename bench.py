@@ -193,6 +193,10 @@ def main():
     ap.add_argument("--tail-cuts", action="store_true",
                     help="time layers with 280 ... 1568 tiles of 128x128 under every way of cutting the last "
                          "partial round of tiles (pinned through the variant name) beside the library's own choice")
+    ap.add_argument("--tail-map", action="store_true",
+                    help="the measurement behind the tail-cut rules: layers with 1 ... 8 rounds of 256 tiles of 128x128 "
+                         "plus every 32nd remainder, on two layer families, each under the library's plan and under "
+                         "every pinned cut of both 128x128 kernels (about a minute)")
     ap.add_argument("--minibatch", action="store_true",
                     help="time the headline layer's geometry at minibatch sizes 4 ... 256")
     ap.add_argument("--block-sizes", action="store_true",
@@ -615,6 +619,54 @@ def main():
                 log(f"[bench]     {k:14s} {r['ms'] * 1e3:8.1f} us {100 * r['frac_peak']:5.1f}%  {r['cut']}")
             del d_in, d_f, out
         result["tail_cuts"] = rows
+
+    if args.tail_map:
+        # For every tile count n = 256 R + r (R = 1 ... 8, r = 16, 48, ... 240) of two layer families
+        # at minibatch 128 -- 3x3 with 128 channels and 256 filters, 5x5 with 96 channels and 256
+        # filters (two filter tiles per pixel) -- the library's plan and every pinned cut.
+        def timed(fn, n):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+        def letter(p):
+            h, t, q, e = p["halved"], p["thirded"], p["quartered"], p["eighthed"]
+            return ("w" if not (h or t or q or e) else "n" if h and e else "m" if h and q else "p" if q and e
+                    else "h" if h else "t" if t else "q" if q else "e")
+        families = {"3x3, 128 -> 256": (128, 256, 3), "5x5, 96 -> 256": (96, 256, 5)}
+        out_map = {}
+        for fam, (nc, no, sk) in families.items():
+            rows = {}
+            for n in range(256 + 16, 9 * 256, 32):
+                px = n // (no // 128)
+                hi = next(h for h in range(int(px ** 0.5), 0, -1) if px % h == 0)
+                wi = px // hi
+                d_in = torch.rand((nc, hi, wi, 128), device="cuda") - 0.5
+                d_f = torch.randn((nc, sk, sk, no), device="cuda") * 0.01
+                out = torch.empty((no, hi, wi, 128), device="cuda")
+                fl = B.mdnn_conv_flops(128, wi, hi, nc, no, sk)
+                res, lib = {}, None
+                for v in [None] + [f"{k}:{c}" for k in ("o128m128", "o128m128k8") for c in "whtqemnp"]:
+                    try:
+                        plan = B.mdnn_describe_launch(128, wi, hi, nc, no, sk, 1, sk // 2, v)
+                    except B.MdnnError:
+                        continue
+                    if v is None:
+                        lib = f"{plan['variant']}:{letter(plan)}"
+                        continue                  # the library's plan is one of the pinned ones: timed once
+                    fn = lambda: B.mdnn_conv_fprop(d_in, d_f, 1, sk // 2, 1.0, out=out, variant=v)
+                    timed(fn, 20)
+                    res[v] = round(fl / min(timed(fn, 10), timed(fn, 10)) / 1e9 / PEAK_FP32_MATRIX_TFLOPS, 4)
+                best = max(res, key=res.get)
+                rows[n] = {"library": lib, "library_frac_peak": res.get(lib), "best": best, "best_frac_peak": res[best], "all": res}
+                log(f"[bench] tail map {fam}: n={n:5d} R={n // 256} r={n % 256:3d} library {lib:14s} "
+                    f"{100 * (res.get(lib) or 0):5.1f}%  best {best:14s} {100 * res[best]:5.1f}%")
+                del d_in, d_f, out
+            out_map[fam] = rows
+        result["tail_map"] = out_map
 
     if args.vgg16:
         # the nine distinct 3x3 shapes of a VGG-16 style network at minibatch 64; random data made on
