@@ -277,18 +277,20 @@ def test_tail_pieces_bitwise(env, case, variant):
     np.testing.assert_array_equal(got, want_out)
 
 
-def test_tail_pieces_along_the_columns_bitwise(env):
-    """The 96x256 tile has three filter blocks per wave and is halved along the columns
-    instead: 320 tiles = one round + 64 tiles cut into 128 half pieces."""
+@pytest.mark.parametrize("variant,split,pieces", [("o96m256", 4, 256), ("o96m256:h", 2, 128)])
+def test_tail_pieces_of_the_96_row_tile_bitwise(env, variant, split, pieces):
+    """The 96x256 tile (eight waves of 48x64) is halved along the filters (48x256 on eight waves of
+    48x32) and quartered along the columns as well (48x128): 320 tiles = one round + 64 tiles cut
+    into 256 quarter pieces by the library's own plan, or into 128 halves when pinned."""
     _, B, oracle = env
     Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha = 128, 34, 22, 4, 96, 3, 1, 0, 1.0
-    plan = B.mdnn_describe_launch(Nb, Wi, Hi, Nc, No, Sk, stride, pad, "o96m256")
-    say(f"[parity-tail-m] plan={plan}")
-    assert plan["tiles"] == 320 and plan["split"] == 2 and plan["pieces"] == 128
+    plan = B.mdnn_describe_launch(Nb, Wi, Hi, Nc, No, Sk, stride, pad, variant)
+    say(f"[parity-tail-96] plan={plan}")
+    assert plan["tiles"] == 320 and plan["split"] == split and plan["pieces"] == pieces
     L = W.custom("tail_m", Nb, Hi, Wi, Nc, No, Sk, stride, pad, alpha)
     inp, filt = W.make_int_inputs(L)
     want = oracle.conv_fprop(inp, filt, stride, pad, alpha, want_abs=False)
-    got = run_gpu(env, L, inp, filt, "o96m256")
+    got = run_gpu(env, L, inp, filt, variant)
     np.testing.assert_array_equal(got, want)
 
 
