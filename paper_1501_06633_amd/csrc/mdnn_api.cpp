@@ -184,7 +184,12 @@ Cut choose_cut(const mdnn::VariantInfo& v, int n_tiles, char force = 0)
         if (c.pieces() > 0) c.n_whole = n_tiles - r;
         return c;
     }
-    take(rounds_of(2) / e2, r, 0, 0);
+    // The other kernels with pieces.  On the three-per-unit 64 x 256 kernel halves (one or two per
+    // unit in front) lose to quarter chains at every round count but two -- by 2 ... 5 points at five
+    // to eight rounds, by 15 at three (65 % against 80 %), where the whole tiles fill their last
+    // wave and the halves displace them; beside two rounds the halves win by 4 ... 6.
+    const bool halves = !(v.est_wg_per_cu >= 3 && v.max_split >= 4) || R == 0 || R == 2;
+    if (halves) take(rounds_of(2) / e2, r, 0, 0);
     // Thirds only beside at most one round of whole tiles (kernels without eighths have none today).
     if (v.thirds && 3 * r <= kComputeUnits && n_tiles < 2 * kComputeUnits) take(0.375 / e3, 0, r, 0);
     if (v.max_split >= 4) take(rounds_of(4) / e4, 0, 0, r);
@@ -217,8 +222,10 @@ double variant_cost(const mdnn::VariantInfo& v, int No, int64_t M)
     double eff;
     if (v.est_wg_per_cu >= 3) {
         const int64_t slots = 3 * kComputeUnits;
+        // (one piece per unit in front was measured to cure it on the 128 x 128 kernel only: the
+        // 64 x 256 kernel with 320 quarter pieces in front of 1024 whole tiles still runs at 72 %)
         const bool partial_second_wave = v.est_wg_per_cu == 3 && n_whole > slots && 8 * (int64_t)n_whole < 13 * slots &&
-                                         n_pieces < kComputeUnits;
+                                         (n_pieces < kComputeUnits || v.max_split < 8);
         eff = tiles <= 2 * kComputeUnits ? v.eff_few : v.eff;
         if (partial_second_wave) eff = 0.82 * v.eff_few;
         // Whole tiles that fill their last wave of 768 exactly leave no room for the tail pieces
