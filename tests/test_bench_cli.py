@@ -19,5 +19,5 @@ def test_help_lists_the_experiments():
                          stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=300)
     assert res.returncode == 0
     for flag in ("--steps", "--warmup", "--gpus", "--block-sizes", "--table1", "--sgemm", "--minibatch",
-                 "--rotating", "--bprop-data", "--bprop-filter", "--vgg16"):
+                 "--rotating", "--bprop-data", "--bprop-filter", "--vgg16", "--variant-sweep", "--tail-cuts", "--tail-map"):
         assert flag in res.stdout, flag
