@@ -51,8 +51,8 @@ typedef enum mdnn_status {
  * conversion); the summation order is unspecified.  Any Nb >= 1 and No >= 1
  * give correct results; the fastest kernels need Nb % 4 == 0 and No % 4 == 0,
  * other values take a variant of the same kernel that copies the operand
- * concerned (filters for No, input patches for Nb) 4 bytes at a time, about a
- * tenth slower.
+ * concerned (filters for No, input patches for Nb) 4 bytes at a time, 5 to 8
+ * per cent slower.
  *
  * The caller owns all three buffers; out must not overlap in or filt.  The
  * call only enqueues work on `stream` (a hipStream_t; NULL = the default

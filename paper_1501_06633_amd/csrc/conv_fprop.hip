@@ -41,7 +41,7 @@ const std::vector<VariantEntry>& entries()
         std::vector<VariantEntry> v;
         const VariantEntry* (*const groups[])(int*) = {conv_variants_a, conv_variants_b, conv_variants_c, conv_variants_d,
                                                        conv_variants_e, conv_variants_f, conv_variants_g,
-                                                       conv_variants_h};
+                                                       conv_variants_h, conv_variants_i};
         for (auto g : groups) {
             int n = 0;
             const VariantEntry* e = g(&n);

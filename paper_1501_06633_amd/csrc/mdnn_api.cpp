@@ -256,8 +256,11 @@ int choose(int Nb, int No, int64_t M, int64_t K)
     for (int i = 0; i < mdnn::variant_count(); ++i) {
         const mdnn::VariantInfo& v = mdnn::variant_info(i);
         if (!variant_usable(v, Nb, No)) continue;
-        // 4-byte copies only for the operand that cannot be copied 16 bytes at a time
-        if ((!v.vec_a && No % 4 == 0) || (!v.vec_b && Nb % 4 == 0)) continue;
+        // 4-byte copies only where 16-byte ones cannot be used.  (With one size off the multiple of 4
+        // the tiles that copy both operands 4 bytes at a time stay in the race: they are rated lower,
+        // but the small one among them is the only small tile such a layer has.)
+        if (Nb % 4 == 0 && No % 4 == 0 && !(v.vec_a && v.vec_b)) continue;
+        if ((!v.vec_a && v.vec_b && No % 4 == 0) || (v.vec_a && !v.vec_b && Nb % 4 == 0)) continue;
         const double c = variant_cost(v, No, M);
         if (best < 0 || c < best_cost) { best = i; best_cost = c; }
     }

@@ -100,6 +100,7 @@ const VariantEntry* conv_variants_e(int* count);
 const VariantEntry* conv_variants_f(int* count);
 const VariantEntry* conv_variants_g(int* count);
 const VariantEntry* conv_variants_h(int* count);
+const VariantEntry* conv_variants_i(int* count);
 
 int                variant_count();
 const VariantInfo& variant_info(int i);

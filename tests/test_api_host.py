@@ -124,8 +124,10 @@ def test_variant_registry_and_choice(L):
                   (7, 9, 9, 3, 5, 3, 1, 1)]:
         assert B.mdnn_choose_variant(*shape) in names
     assert B.mdnn_choose_variant(7, 9, 9, 3, 5, 3, 1, 1).endswith("s")     # scalar-load variant
-    assert B.mdnn_choose_variant(64, 56, 56, 256, 250, 3, 1, 1) == "o128m128a"    # only the filter count is odd
-    assert B.mdnn_choose_variant(50, 56, 56, 256, 256, 3, 1, 1) == "o128m128b"    # only the minibatch is
+    assert B.mdnn_choose_variant(64, 56, 56, 256, 250, 3, 1, 1) == "o128m128k8a"  # only the filter count is off the multiple of 4
+    assert B.mdnn_choose_variant(50, 56, 56, 256, 256, 3, 1, 1) == "o128m128k8b"  # only the minibatch is
+    assert B.mdnn_choose_variant(50, 56, 56, 256, 250, 3, 1, 1) == "o128m128s"    # both
+    assert B.mdnn_choose_variant(6, 9, 10, 5, 40, 3, 2, 1) == "o64m64s"           # a small layer: the only small tile it can take
     assert B.mdnn_choose_variant(8, 2, 2, 1, 1, 3, 1, 0) is None          # invalid geometry
 
 
