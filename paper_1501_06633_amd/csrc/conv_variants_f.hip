@@ -24,7 +24,7 @@ const VariantEntry kGroup[] = {
     make_entry<C_o64m64s>("o64m64s", 4, 0.76f, 0.70f),
     // the 128 x 128 tile fed by 4-byte copies, sixteen copies per thread and slab instead of four:
     // 83 % with Nb = 50, 79.5 % with No = 250
-    make_entry<C_o128m128s>("o128m128s", 2, 0.83f, 0.78f, 2048),
+    make_entry<C_o128m128s, 4>("o128m128s", 2, 0.83f, 0.78f, 2048),
 };
 
 }  // namespace

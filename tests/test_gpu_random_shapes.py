@@ -90,7 +90,7 @@ def test_pinned_cuts_on_random_shapes_bitwise():
 
     pinned = ["o128m128:H", "o128m128:T", "o128m128:Q", "o128m128:t", "o128m128k8:H", "o128m128k8:Q",
               "o96m256:H", "o96m256:h", "o96m256:Q", "o96m256:q",
-              "o128m128a:H", "o128m128a:Q", "o128m128b:H", "o128m128b:Q", "o128m128k8a:Q", "o128m128k8a:h", "o128m128k8b:Q", "o128m128k8b:q", "o128m128k8:m", "o128m128k8:n", "o128m128k8:p", "o128m128k8:E", "o128m128:e", "o64m256k8:H", "o64m256k8:Q", "o64m256k8:q", "o48m128:w", "o64m512:w"]
+              "o128m128a:H", "o128m128a:Q", "o128m128b:H", "o128m128b:Q", "o128m128k8a:Q", "o128m128k8a:h", "o128m128k8b:Q", "o128m128k8b:q", "o128m128s:H", "o128m128s:Q", "o128m128k8:m", "o128m128k8:n", "o128m128k8:p", "o128m128k8:E", "o128m128:e", "o64m256k8:H", "o64m256k8:Q", "o64m256k8:q", "o48m128:w", "o64m512:w"]
     rng = np.random.default_rng(4096)
     runs = paired = 0
     for it in range(30):
