@@ -170,3 +170,52 @@ def test_default_plans_with_one_to_five_rounds_of_tiles_bitwise():
     for need in [("halved",), ("quartered",), ("eighthed",), ("thirded",), ("halved", "eighthed"), ("halved", "quartered")]:
         assert need in cuts, (need, sorted(cuts))
     assert any(first and behind for _, _, first, behind in seen)      # pieces in front of and behind the whole tiles
+
+
+def test_default_plans_with_sizes_off_the_multiple_of_four_bitwise():
+    """Forty seeded shapes with one to four rounds of 128 x 128 tiles whose minibatch, filter count
+    or both are no multiples of 4, under the library's own plan: the tiles with one or both
+    operands in 4-byte copies, their half and quarter pieces and ragged filter tiles all occur
+    (asserted); forward result and data gradient bit for bit on integer data."""
+    import torch
+    from paper_1501_06633_amd import binding as B
+    import oracle
+
+    rng = np.random.default_rng(31415)
+    seen = set()
+    for it in range(40):
+        kind = it % 3                                       # 0: only No odd, 1: only Nb, 2: both
+        Nb = int(rng.choice([32, 64]) if kind == 0 else rng.choice([6, 30, 50, 66]))
+        No = int(rng.choice([128, 256]) if kind == 1 else rng.choice([130, 202, 250, 257]))
+        want_tiles = int(rng.integers(257, 1100))
+        col_tiles = max(1, want_tiles // -(-No // 128))
+        pixels = max(1, col_tiles * 128 // Nb)
+        Ho = int(rng.integers(1, 24))
+        Wo = max(1, pixels // Ho)
+        Sk = int(rng.choice([1, 3]))
+        pad = int(rng.integers(0, Sk))
+        Hi, Wi = Ho + Sk - 1 - 2 * pad, Wo + Sk - 1 - 2 * pad
+        if Hi < 1 or Wi < 1:
+            Hi, Wi, pad = Ho + Sk - 1, Wo + Sk - 1, 0
+        Nc = int(rng.integers(1, 4))
+        alpha = float(rng.choice([1.0, 0.5]))
+        plan = B.mdnn_describe_launch(Nb, Wi, Hi, Nc, No, Sk, 1, pad)
+        cut = tuple(k for k in ("halved", "thirded", "quartered", "eighthed") if plan[k])
+        seen.add((plan["variant"], cut))
+        Wo2 = Wi + 2 * pad - Sk + 1
+        Ho2 = Hi + 2 * pad - Sk + 1
+        x = rng.integers(-4, 5, size=(Nc, Hi, Wi, Nb)).astype(np.float32)
+        w = rng.integers(-4, 5, size=(Nc, Sk, Sk, No)).astype(np.float32)
+        g = rng.integers(-4, 5, size=(No, Ho2, Wo2, Nb)).astype(np.float32)
+        what = f"case={it} Nb={Nb} Hi={Hi} Wi={Wi} Nc={Nc} No={No} Sk={Sk} pad={pad} alpha={alpha} plan={plan}"
+        print(what, flush=True)
+        d_x, d_w, d_g = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), torch.from_numpy(g).cuda()
+        y = B.mdnn_conv_fprop(d_x, d_w, 1, pad, alpha)
+        dx = B.mdnn_conv_bprop_data(d_g, d_w, (Hi, Wi), 1, pad, alpha)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(y.cpu().numpy(), oracle.conv_fprop(x, w, 1, pad, alpha, want_abs=False), err_msg=what)
+        np.testing.assert_array_equal(dx.cpu().numpy(), oracle.conv_bprop_data(g, w, (Hi, Wi), 1, pad, alpha, want_abs=False),
+                                      err_msg=what)
+    variants = {v for v, _ in seen}
+    assert {"o128m128k8a", "o128m128k8b", "o128m128s"} <= variants or {"o128m128a", "o128m128b", "o128m128s"} <= variants, sorted(seen)
+    assert any(c for v, c in seen if v[-1] in "ab") and any(c for v, c in seen if v == "o128m128s"), sorted(seen)
