@@ -150,8 +150,8 @@ Cut choose_cut(const mdnn::VariantInfo& v, int n_tiles, char force = 0)
     const int R = n_tiles / kComputeUnits;
     if (v.max_split >= 8 && R >= 1) {
         // The two 128 x 128 kernels, which have every piece size.  Measured over R = 1 ... 8 rounds
-        // and r = 8 ... 248 left-over tiles on four layer families (3x3 with 128, 256 and 384
-        // filters, 5x5 with 256), every cut pinned in turn.  With pieces of one size the best cut
+        // and r = 8 ... 248 left-over tiles on five layer families (3x3 with 128, 256, 384
+        // and 512 filters, 5x5 with 256), every cut pinned in turn.  With pieces of one size the best cut
         // follows the rows on the busiest unit at every R:
         //     r <= 32 eighths (16 rows) | <= 64 quarters (32) | <= 128 halves (64) | <= 192 quarters in
         //     chains of up to three | beyond: whole tiles,
@@ -163,8 +163,10 @@ Cut choose_cut(const mdnn::VariantInfo& v, int n_tiles, char force = 0)
         //   - three-per-unit kernel: the last wave of 768 must hold only 256 whole tiles (R mod 3 = 1;
         //     +1 ... +6 points over chains and halves on all four families); with 512 in it (R = 2, 5)
         //     the half pairings fall to 65 ... 82 %, the quarter-and-eighth pairing still holds;
-        //   - two-per-unit kernel: steady on the 3x3 families, but 79.8 % against 89.5 % and 84.5 %
-        //     against 89.5 % on two 5x5 layers five rounds long -- not taken.
+        //   - two-per-unit kernel: the half and the eighth are steady at every R on all five families
+        //     (84 ... 92 %, 3 ... 6 points over quarter chains) and are taken; the half and the quarter
+        //     fall to 79.8 % against 89.5 % and 84.5 % against 89.5 % on two 5x5 layers five rounds
+        //     long -- not taken.
         // Whole tiles that fill their last wave exactly (three-per-unit kernel, R mod 3 = 0) leave
         // no room for any piece in front: halves swing between 75 and 91 % from shape to shape,
         // eighths between 67 and 82 %; quarters, alone or in chains, are the steady choice (83 ... 91 %).
@@ -179,7 +181,7 @@ Cut choose_cut(const mdnn::VariantInfo& v, int n_tiles, char force = 0)
         else if (r <= 85 && v.thirds && R % 2 == 1) take(0.375 / e3, 0, r, 0);
         else if (r <= 96 && three && !full_wave)   take(0.40, 0, 0, 64, r - 64, true);
         else if (r <= 128)                         take(0.5 / e2, r, 0, 0);
-        else if (r <= 160 && three && R % 3 == 1)  take(0.65, 128, 0, 0, r - 128, true);
+        else if (r <= 160 && (!three || R % 3 == 1)) take(three || R >= 2 ? 0.65 : 0.72, 128, 0, 0, r - 128, true);
         else if (r <= 192 && three && R % 3 == 1)  take(0.78, 128, 0, r - 128, 0, true);
         else if (r <= 192)                         take(rounds_of(4) / e4, 0, 0, r);
         if (c.pieces() > 0) c.n_whole = n_tiles - r;

@@ -209,7 +209,7 @@ def test_how_the_last_round_is_cut(L):
     128, quarters in chains up to 192, then whole tiles; thirds (the deep-slab kernel) for 65 ... 85
     when R is odd.  Pairings of two sizes per unit (three-per-unit kernel): a quarter and an eighth
     for 65 ... 96 unless R mod 3 = 0, a half and an eighth (to 160) or a quarter (to 192) when
-    R mod 3 = 1.  R mod 3 = 0 up to eight rounds on that kernel: quarters only."""
+    R mod 3 = 1; the two-per-unit kernel takes the half and the eighth at every R.  R mod 3 = 0 up to eight rounds on that kernel: quarters only."""
     def cut(r, variant, R=1):
         d = B.mdnn_describe_launch(128, 2 + 1, 2 + (256 * R + r), 4, 128, 3, 1, 0, variant)
         assert d["tiles"] == 256 * R + r and d["whole"] + d["halved"] + d["thirded"] + d["quartered"] + d["eighthed"] == d["tiles"]
@@ -232,7 +232,8 @@ def test_how_the_last_round_is_cut(L):
             else:
                 assert cut(65, v, R) == ("65t" if R % 2 else "65h") and cut(85, v, R) == ("85t" if R % 2 else "85h")
                 assert cut(86, v, R) == "86h" and cut(128, v, R) == "128h"
-                assert cut(129, v, R) == "129q" and cut(192, v, R) == "192q"
+                assert cut(129, v, R) == "128h1e" and cut(160, v, R) == "128h32e"
+                assert cut(161, v, R) == "161q" and cut(192, v, R) == "192q"
     # where the pieces go: pairings all in front, single sizes up to one per unit in front of two or more rounds
     d = B.mdnn_describe_launch(128, 2 + 1, 2 + 392, 4, 128, 3, 1, 0, "o128m128k8")
     assert (d["whole"], d["pieces"], d["pieces_first"]) == (256, 320, 320)

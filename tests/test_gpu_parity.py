@@ -246,12 +246,13 @@ TAILS = [
     ("quarters_ragged", 64, 11, 40, 6, 200, 3, 1, 1, 2.0, 4, (128, 0, 56, 0)),   # padded, ragged filter tile, 2 pixels per tile; 440 tiles
     ("thirds",    128, 14, 30,  8, 128, 3, 1, 0, 1.0,  3, (0, 0, 64, 16)),      # 336 tiles: 80 left over -> 48 + 48 + 32 rows; a quarter and an eighth per unit
     ("thirds_ragged", 64, 12, 28, 6, 200, 3, 1, 1, 2.0, 3, (0, 0, 64, 16)),     # 336 tiles, the second filter tile has 72 rows
-    # 392 tiles, 136 left over: up to three quarters per unit; the three-per-unit kernel pairs halves with eighths
-    ("one_round_136", 128, 16, 30, 8, 128, 3, 1, 0, 0.5, 4, (128, 0, 0, 8)),
+    # 392 tiles, 136 left over: both kernels pair halves with eighths
+    ("one_round_136", 128, 16, 30, 8, 128, 3, 1, 0, 0.5, (128, 0, 0, 8), (128, 0, 0, 8)),
+    ("one_round_164", 128, 16, 32, 8, 128, 3, 1, 0, 0.5, 4, (128, 0, 36, 0)),   # 420 tiles: quarter chains; halves with quarters
     ("one_round_89", 128, 17, 25, 8, 128, 3, 1, 0, 0.5, 2, (0, 0, 64, 25)),   # 345 tiles: halves; quarters paired with eighths
     ("one_round_24", 128, 12, 30, 8, 128, 3, 1, 0, 2.0, 8, 4),                 # 280 tiles: eighths beside one round on the deep-slab kernel
     ("two_rounds_28", 128, 22, 29, 8, 128, 3, 1, 0, 1.0, 8, 8),                # 540 tiles: eighths in front of two rounds
-    ("two_rounds_136", 128, 20, 38, 8, 128, 3, 1, 0, 0.5, 4, 4),    # 648 tiles: quarter chains on both
+    ("two_rounds_136", 128, 20, 38, 8, 128, 3, 1, 0, 0.5, (128, 0, 0, 8), 4),    # 648 tiles: halves with eighths; quarter chains
 ]
 
 
@@ -297,7 +298,8 @@ def test_tail_pieces_of_the_96_row_tile_bitwise(env, variant, split, pieces):
 @pytest.mark.parametrize("variant,No,want_plan", [
     ("o128m128k8", 768, dict(tiles=588, whole=512, split=0, quartered=64, eighthed=12, pieces=352, pieces_first=352)),   # a pairing: all pieces in front
     ("o128m128k8:h", 768, dict(tiles=588, whole=512, split=2, pieces=152, pieces_first=152)),  # halves: all in front
-    ("o128m128", 1280, dict(tiles=910, whole=768, split=4, pieces=568, pieces_first=256)),    # 256 in front, 312 behind
+    ("o128m128", 1280, dict(tiles=910, whole=768, split=0, halved=128, eighthed=14, pieces=368, pieces_first=368)),   # a pairing on the other kernel
+    ("o128m128:q", 1280, dict(tiles=910, whole=768, split=4, pieces=568, pieces_first=256)),    # 256 in front, 312 behind
     # every tile in thirds (the cut pinned through the variant name): 48- and 32-row pieces only
     ("o128m128:T", 256, dict(tiles=182, whole=0, split=3, thirded=182, pieces=546, pieces_first=0)),
     # thirds of the last round with two rounds of whole tiles in front: the pieces go first
