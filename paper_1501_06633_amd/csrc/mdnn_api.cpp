@@ -17,6 +17,10 @@ constexpr int     kStripRows = 8;               // image rows per strip of the 2
 constexpr int64_t kFourGiB = (int64_t)1 << 32;
 constexpr int     kWideTileMaxK = 64;           // ... and below this the 64 x 512 tile is taken
 constexpr int     kStreamOutMaxK = 128;         // contractions this short are bound by writing the output
+constexpr int64_t kStreamOutMinBytes = (int64_t)16 << 20;   // an output of half the 8 x 4 MB of L2 or more would not
+                                                // stay there beside the operands: it is streamed past them
+                                                // (never slower; 0 ... 2.6 points at K = 576 and 0 ... 0.8 on longer
+                                                // contractions, depending on the machine the run landed on)
 constexpr int     kMaxSlab = 64;                // no tile variant stages more rows of k than this at once
 
 struct Geometry {
@@ -362,7 +366,7 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
     const int kpad = div_up(g.K, vi.kslab) * vi.kslab;
     p.tab_cap = kpad < vi.max_tab ? kpad : vi.max_tab;
     p.scat_stride = 0;  p.scat_Nc = 0;  p.scat_Hi = 0;  p.scat_Wi = 0;  p.scat_pad = 0;
-    p.stream_out = g.K <= kStreamOutMaxK ? 1 : 0;
+    p.stream_out = (g.K <= kStreamOutMaxK || g.out_bytes >= kStreamOutMinBytes) ? 1 : 0;
     p.in_bytes = (uint32_t)g.in_bytes;
     p.filt_bytes = (uint32_t)g.filt_bytes;
     p.alpha = 0.0f;

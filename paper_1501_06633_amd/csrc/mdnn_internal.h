@@ -60,7 +60,7 @@ struct ConvParams {
     // out[c][qy * scat_stride + ry - scat_pad][qx * scat_stride + rx - scat_pad][n] of a
     // [scat_Nc][scat_Hi][scat_Wi][Nb] tensor (dropped where that pixel does not exist).
     int scat_stride, scat_Nc, scat_Hi, scat_Wi, scat_pad;
-    int stream_out;      // 1: whole tiles store with the non-temporal hint (output-bound layers)
+    int stream_out;      // 1: whole tiles store with the non-temporal hint (short contractions, large outputs)
     uint32_t in_bytes;   // byte size of in   (buffer-resource range: loads beyond it return 0)
     uint32_t filt_bytes; // byte size of filt
     float alpha;
