@@ -128,6 +128,11 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
     constexpr int ACCESS_A = 4 * VWA, ACCESS_B = 4 * VWB;    // bytes per lane per global -> LDS copy
     typedef typename VecOf<RB>::type BVec;
 
+    // A tile's start-up (column set-up, offset table, first copies) issues ahead of the older
+    // workgroups' slab loops on the same SIMDs, which otherwise leave a young wave only the issue
+    // cycles they do not use (a fifth of a tile's time passed before its first matrix instruction);
+    // the priority drops back once the first slab is there.  +0.5 ... 1.2 % where K is a few hundred.
+    __builtin_amdgcn_s_setprio(3);
     u32x2* tab = reinterpret_cast<u32x2*>(lds + C::ring_bytes);   // [tab_cap] {byte offset, tap id}
     const uint32_t lds_base = (uint32_t)(uintptr_t)LDS_PTR(lds);
     const uint32_t tab_base = lds_base + C::ring_bytes;
@@ -371,6 +376,7 @@ __device__ __forceinline__ void conv_tile(const ConvParams& p, unsigned char* ld
                 });
             }
             bare_barrier();
+            __builtin_amdgcn_s_setprio(0);
             request(I0{}, I0{}, I0{});
 
             // One slab.  `steady` = slabs s+1 .. s+NS all exist, so the barrier, the
