@@ -101,10 +101,9 @@ bool variant_usable(const mdnn::VariantInfo& v, int Nb, int No)
 //   r <= 64: quarters (1.25 tile times for the round instead of 2);
 //   r <= 85: thirds (1.375; 338 tiles of 128 x 128 on a 13 x 13 layer: 80 -> 86 % of peak);
 //   r <= 128: halves (1.5);
-//   r <= 192: quarters in chains of up to three (a mixture that gives every unit a half or
-//       a third plus a quarter has fewer rows on the busiest unit, but its second pieces run
-//       alone: 533 us against 488 us on a 14 x 14 layer with 392 tiles) -- except beside a single
-//       round on a three-per-unit kernel, see the end of choose_cut();
+//   r <= 192: quarters in chains of up to three, or -- where the whole tiles leave room for
+//       two pieces per unit in front of them -- a half paired with an eighth or a quarter (see
+//       choose_cut() for where that is);
 // each weighed by the piece's relative efficiency and taken only if it beats the coarser
 // choice by a margin.
 struct Cut {
@@ -165,7 +164,7 @@ Cut choose_cut(const mdnn::VariantInfo& v, int n_tiles, char force = 0)
         // unit (<= 96: a quarter and an eighth; <= 160: a half and an eighth; <= 192: a half and a
         // quarter; all pieces in front) need room for up to 512 pieces beside the whole tiles:
         //   - three-per-unit kernel: the last wave of 768 must hold only 256 whole tiles (R mod 3 = 1;
-        //     +1 ... +6 points over chains and halves on all four families); with 512 in it (R = 2, 5)
+        //     +1 ... +6 points over chains and halves on all five families); with 512 in it (R = 2, 5)
         //     the half pairings fall to 65 ... 82 %, the quarter-and-eighth pairing still holds;
         //   - two-per-unit kernel: the half and the eighth are steady at every R on all five families
         //     (84 ... 92 %, 3 ... 6 points over quarter chains) and are taken; the half and the quarter
@@ -293,7 +292,7 @@ mdnn_status plan(int Nb, int Wi, int Hi, int Nc, int No, int Sk, int stride, int
     if (!variant || !variant[0] || std::strcmp(variant, "auto") == 0) {
         v = choose(Nb, No, g.M, g.K);
     } else {
-        // "name" or "name:c" with c one of w h t q e m n H T Q E (see choose_cut)
+        // "name" or "name:c" with c one of w h t q e m n p H T Q E (see choose_cut)
         char name[32];
         const char* colon = std::strchr(variant, ':');
         const size_t len = colon ? (size_t)(colon - variant) : std::strlen(variant);
