@@ -219,3 +219,45 @@ def test_default_plans_with_sizes_off_the_multiple_of_four_bitwise():
     variants = {v for v, _ in seen}
     assert {"o128m128k8a", "o128m128k8b", "o128m128s"} <= variants or {"o128m128a", "o128m128b", "o128m128s"} <= variants, sorted(seen)
     assert any(c for v, c in seen if v[-1] in "ab") and any(c for v, c in seen if v == "o128m128s"), sorted(seen)
+
+
+def test_mid_size_random_shapes_all_three_calls_bitwise():
+    """Seventy seeded shapes with a hundred to a few thousand tiles -- minibatches 30, 32, 50, 64, 100
+    and 128, 64 to 512 filters, 1x1 to 5x5, strides 1 and 2, pads up to Sk + 1 -- through the forward
+    call and both gradients under the library's own plans (whatever tail cut, copy width and
+    workspace split they take), integer data, bit for bit."""
+    import torch
+    from paper_1501_06633_amd import binding as B
+    import oracle
+
+    rng = np.random.default_rng(21)
+    cuts = set()
+    for it in range(70):
+        Nb = int(rng.choice([32, 64, 128, 50, 30, 100]))
+        Sk = int(rng.choice([1, 3, 3, 3, 5]))
+        stride = int(rng.choice([1, 1, 1, 2]))
+        pad = int(rng.integers(0, Sk + 2))
+        Hi, Wi = int(rng.integers(12, 44)), int(rng.integers(12, 44))
+        Nc = int(rng.integers(1, 7))
+        No = int(rng.choice([64, 96, 128, 192, 250, 256, 384, 512]))
+        alpha = float(rng.choice([1.0, 0.5]))
+        Wo, Ho = oracle.out_dims(Wi, Hi, Sk, stride, pad)
+        x = rng.integers(-4, 5, size=(Nc, Hi, Wi, Nb)).astype(np.float32)
+        w = rng.integers(-4, 5, size=(Nc, Sk, Sk, No)).astype(np.float32)
+        g = rng.integers(-4, 5, size=(No, Ho, Wo, Nb)).astype(np.float32)
+        d_x, d_w, d_g = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), torch.from_numpy(g).cuda()
+        plan = B.mdnn_describe_launch(Nb, Wi, Hi, Nc, No, Sk, stride, pad)
+        what = (f"case={it} Nb={Nb} Hi={Hi} Wi={Wi} Nc={Nc} No={No} Sk={Sk} stride={stride} pad={pad} alpha={alpha} "
+                f"variant={plan['variant']} tiles={plan['tiles']}")
+        print(what, flush=True)
+        cuts.add((plan["variant"], plan["halved"] > 0, plan["thirded"] > 0, plan["quartered"] > 0, plan["eighthed"] > 0))
+        y = B.mdnn_conv_fprop(d_x, d_w, stride, pad, alpha)
+        dw = B.mdnn_conv_bprop_filter(d_x, d_g, Sk, stride, pad, alpha)
+        dx = B.mdnn_conv_bprop_data(d_g, d_w, (Hi, Wi), stride, pad, alpha)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(y.cpu().numpy(), oracle.conv_fprop(x, w, stride, pad, alpha, want_abs=False), err_msg=what)
+        np.testing.assert_array_equal(dw.cpu().numpy(), oracle.conv_bprop_filter(x, g, Sk, stride, pad, alpha, want_abs=False),
+                                      err_msg=what)
+        np.testing.assert_array_equal(dx.cpu().numpy(),
+                                      oracle.conv_bprop_data(g, w, (Hi, Wi), stride, pad, alpha, want_abs=False), err_msg=what)
+    assert len(cuts) >= 8, cuts          # the seed really spreads over kernels and cuts
