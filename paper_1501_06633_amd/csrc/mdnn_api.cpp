@@ -167,7 +167,9 @@ Cut choose_cut(const mdnn::VariantInfo& v, int n_tiles, char force = 0)
         //     +1 ... +6 points over chains and halves on all five families); with 512 in it (R = 2, 5)
         //     the half pairings fall to 65 ... 82 %, the quarter-and-eighth pairing still holds;
         //   - two-per-unit kernel: the half and the eighth are steady at every R on all five families
-        //     (84 ... 92 %, 3 ... 6 points over quarter chains) and are taken; the half and the quarter
+        //     (84 ... 92 %, 3 ... 6 points over quarter chains) and are taken; so is the quarter and the
+        //     eighth for two to eight rounds (0.3 ... 4.7 points over halves in all 24 measured cases; beside
+        //     a single round it falls to 49 ... 52 % on three of the families); the half and the quarter
         //     fall to 79.8 % against 89.5 % and 84.5 % against 89.5 % on two 5x5 layers five rounds
         //     long -- not taken.
         // Whole tiles that fill their last wave exactly (three-per-unit kernel, R mod 3 = 0) leave
@@ -182,7 +184,7 @@ Cut choose_cut(const mdnn::VariantInfo& v, int n_tiles, char force = 0)
         } else if (r <= 32 && !(three && R == 1) && !full_wave) take(0.125 / e8, 0, 0, 0, r);
         else if (r <= 64)                          take(0.25 / e4, 0, 0, r);
         else if (r <= 85 && v.thirds && R % 2 == 1) take(0.375 / e3, 0, r, 0);
-        else if (r <= 96 && three && !full_wave)   take(0.40, 0, 0, 64, r - 64, true);
+        else if (r <= 96 && (three ? !full_wave : R >= 2 && R <= 8)) take(0.40, 0, 0, 64, r - 64, true);
         else if (r <= 128)                         take(0.5 / e2, r, 0, 0);
         else if (r <= 160 && (!three || R % 3 == 1)) take(three || R >= 2 ? 0.65 : 0.72, 128, 0, 0, r - 128, true);
         else if (r <= 192 && three && R % 3 == 1)  take(0.78, 128, 0, r - 128, 0, true);
@@ -222,7 +224,8 @@ double variant_cost(const mdnn::VariantInfo& v, int No, int64_t M)
     // of them a second time (up to 1248) with fewer than one piece per unit in front of them, the
     // tiles beyond the first wave land wherever slots free first, two on one unit while others
     // idle.  128x128: 73-82 % at 992 ... 1120 tiles against 93 % at 768, at 1088 with 256 pieces in
-    // front, and from 1248 on; 96x128: 91 % at 768 tiles, 74 % at 1024.  (The small tiles at four
+    // front (with 224 it is 75 ... 83 % on three families and 90 % on two), and from 1248 on;
+    // 96x128: 91 % at 768 tiles, 74 % at 1024.  (The small tiles at four
     // and more per unit show no such dip: 32x128 follows plain rounds of 256.)
     const int64_t n_pieces = cut.pieces();
     double eff;

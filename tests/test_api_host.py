@@ -209,7 +209,8 @@ def test_how_the_last_round_is_cut(L):
     128, quarters in chains up to 192, then whole tiles; thirds (the deep-slab kernel) for 65 ... 85
     when R is odd.  Pairings of two sizes per unit (three-per-unit kernel): a quarter and an eighth
     for 65 ... 96 unless R mod 3 = 0, a half and an eighth (to 160) or a quarter (to 192) when
-    R mod 3 = 1; the two-per-unit kernel takes the half and the eighth at every R.  R mod 3 = 0 up to eight rounds on that kernel: quarters only."""
+    R mod 3 = 1; the two-per-unit kernel takes the half and the eighth at every R and, for two to
+    eight rounds, the quarter and the eighth where it has no thirds.  R mod 3 = 0 up to eight rounds on that kernel: quarters only."""
     def cut(r, variant, R=1):
         d = B.mdnn_describe_launch(128, 2 + 1, 2 + (256 * R + r), 4, 128, 3, 1, 0, variant)
         assert d["tiles"] == 256 * R + r and d["whole"] + d["halved"] + d["thirded"] + d["quartered"] + d["eighthed"] == d["tiles"]
@@ -230,8 +231,11 @@ def test_how_the_last_round_is_cut(L):
                 assert cut(161, v, R) == ("128h33q" if R % 3 == 1 else "161q") and cut(192, v, R) == ("128h64q" if R % 3 == 1 else "192q")
                 assert cut(100, v, R) == ("100q" if full and R <= 8 else "100h") and cut(128, v, R) == ("128q" if full and R <= 8 else "128h")
             else:
-                assert cut(65, v, R) == ("65t" if R % 2 else "65h") and cut(85, v, R) == ("85t" if R % 2 else "85h")
-                assert cut(86, v, R) == "86h" and cut(128, v, R) == "128h"
+                pairs = 2 <= R <= 8       # a quarter and an eighth per unit where thirds are not taken
+                assert cut(65, v, R) == ("65t" if R % 2 else "64q1e" if pairs else "65h")
+                assert cut(85, v, R) == ("85t" if R % 2 else "64q21e" if pairs else "85h")
+                assert cut(86, v, R) == ("64q22e" if pairs else "86h") and cut(96, v, R) == ("64q32e" if pairs else "96h")
+                assert cut(97, v, R) == "97h" and cut(128, v, R) == "128h"
                 assert cut(129, v, R) == "128h1e" and cut(160, v, R) == "128h32e"
                 assert cut(161, v, R) == "161q" and cut(192, v, R) == "192q"
     # where the pieces go: pairings all in front, single sizes up to one per unit in front of two or more rounds
