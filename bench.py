@@ -37,13 +37,13 @@ WARM_MS_FLOOR = 100.0
 TRAFFIC_SOURCE = "profiles/conv_fprop_hbm_traffic_pmc.txt"
 PLAN_KEYS = ("variant", "tiles", "whole", "halved", "thirded", "quartered", "eighthed", "pieces_first", "table_entries")
 RECORDED_TRAFFIC = {
-    "vgg":   {"bytes": 741.5e6, "plan": {"variant": "o128m128k8", "tiles": 3136, "whole": 3072, "halved": 0, "thirded": 0,
+    "vgg":   {"bytes": 740.0e6, "plan": {"variant": "o128m128k8", "tiles": 3136, "whole": 3072, "halved": 0, "thirded": 0,
                                          "quartered": 64, "eighthed": 0, "pieces_first": 256, "table_entries": 2304}},
-    "conv1": {"bytes": 265.4e6, "plan": {"variant": "o96m256", "tiles": 1513, "whole": 1513, "halved": 0, "thirded": 0,
+    "conv1": {"bytes": 265.5e6, "plan": {"variant": "o96m256", "tiles": 1513, "whole": 1513, "halved": 0, "thirded": 0,
                                          "quartered": 0, "eighthed": 0, "pieces_first": 0, "table_entries": 368}},
-    "conv2": {"bytes": 291.4e6, "plan": {"variant": "o128m128k8", "tiles": 1458, "whole": 1280, "halved": 0, "thirded": 0,
+    "conv2": {"bytes": 291.0e6, "plan": {"variant": "o128m128k8", "tiles": 1458, "whole": 1280, "halved": 0, "thirded": 0,
                                          "quartered": 178, "eighthed": 0, "pieces_first": 256, "table_entries": 2400}},
-    "conv3": {"bytes": 105.3e6, "plan": {"variant": "o128m128", "tiles": 507, "whole": 507, "halved": 0, "thirded": 0,
+    "conv3": {"bytes": 105.4e6, "plan": {"variant": "o128m128", "tiles": 507, "whole": 507, "halved": 0, "thirded": 0,
                                          "quartered": 0, "eighthed": 0, "pieces_first": 0, "table_entries": 2304}},
 }
 
